@@ -1,0 +1,484 @@
+"""Pins of the fp64 oracle against things other than itself (CPU only).
+
+Each test names what it fixes.  The pins are: closed forms (ridge regression,
+softmax regression), dense linear algebra on tiny problems, finite differences
+of *lower-order* quantities, symmetry/linearity invariants, and PyTorch's
+fp64 autograd applied to a forward-only statement of the costs (the
+derivatives there come from the library's reverse mode, not from the
+hand-derived forward-over-reverse formulas under test).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import betty_oracle as orc
+from paper_2207_02849_amd import workloads as wk
+from tests.util import oracle_problem, rel_l2
+
+
+# ---------------------------------------------------------------- helpers
+
+def dense_hessian_by_hvp(prob, w, lam):
+    d = prob.d
+    H = np.zeros((d, d))
+    for j in range(d):
+        e = np.zeros(d)
+        e[j] = 1.0
+        H[:, j] = orc.hvp(prob, w, lam, e)
+    return H
+
+
+def torch_costs(wl):
+    """Forward-only torch statement of L_L and L_U (fp64), following the paper's
+    reweighting listing (per-sample CE, weight net on the detached loss, mean)."""
+    dims, act = wl.dims, wl.act
+    Xtr = torch.tensor(wl.X_tr, dtype=torch.float64)
+    Xva = torch.tensor(wl.X_val, dtype=torch.float64)
+
+    def net(w, X):
+        o, a = 0, X
+        L = len(dims) - 1
+        for l in range(L):
+            W = w[o:o + dims[l] * dims[l + 1]].reshape(dims[l], dims[l + 1])
+            o += dims[l] * dims[l + 1]
+            z = a @ W
+            if wl.has_bias:
+                z = z + w[o:o + dims[l + 1]]
+                o += dims[l + 1]
+            if l < L - 1:
+                if act == "relu":
+                    a = torch.relu(z)
+                elif act == "gelu":
+                    a = torch.nn.functional.gelu(z)
+                else:
+                    a = z
+            else:
+                a = z
+        return a
+
+    def per_sample(w, X, y, t):
+        out = net(w, X)
+        if wl.loss == "ce":
+            return torch.nn.functional.cross_entropy(out, torch.tensor(y, dtype=torch.long), reduction="none")
+        return ((out - torch.tensor(t, dtype=torch.float64)) ** 2).sum(dim=1)
+
+    def lower(w, lam):
+        loss = per_sample(w, Xtr, wl.y_tr, wl.t_tr)
+        if wl.hp == "l2":
+            return loss.mean() + (torch.exp(lam) * w * w).sum()
+        H = wl.wnet_hidden
+        u1, b1, u2, b2 = lam[:H], lam[H:2 * H], lam[2 * H:3 * H], lam[3 * H]
+        x = loss.detach().reshape(-1, 1)
+        hid = torch.relu(x * u1 + b1)
+        weight = torch.sigmoid(hid @ u2 + b2)
+        return torch.mean(weight * loss)
+
+    def upper(w):
+        return per_sample(w, Xva, wl.y_val, wl.t_val).mean()
+
+    return lower, upper
+
+
+TINY = [
+    dict(kind="l2", act="gelu", loss="ce"),
+    dict(kind="l2", act="relu", loss="ce"),
+    dict(kind="l2", act="none", loss="mse", dims=(6, 2), has_bias=False),
+    dict(kind="l2", act="gelu", loss="mse", dims=(4, 5, 2)),
+    dict(kind="reweight", act="gelu", loss="ce"),
+    dict(kind="reweight", act="relu", loss="ce", dims=(6, 5, 4), batch=9),
+]
+
+
+def _vec(seed, n):
+    return np.random.default_rng(seed).standard_normal(n)
+
+
+# ---------------------------------------------------------------- P1/P2/P4/P10: ridge
+
+def ridge_setup():
+    wl = wk.config(1)
+    prob = oracle_problem(wl)
+    lam = wl.lam.astype(np.float64)
+    w_star = orc.ridge_solve(wl.X_tr, wl.t_tr, lam)
+    return wl, prob, lam, w_star
+
+
+def ridge_closed_form(wl, lam, w_star):
+    """-diag(2 e^lam w*) (2 X'X/n + 2 diag e^lam)^-1 grad_w L_val   (fp64, dense)."""
+    X = wl.X_tr.astype(np.float64)
+    Xv = wl.X_val.astype(np.float64)
+    tv = wl.t_val.astype(np.float64).ravel()
+    n, nv = X.shape[0], Xv.shape[0]
+    H = 2.0 * X.T @ X / n + 2.0 * np.diag(np.exp(lam))
+    g = 2.0 * Xv.T @ (Xv @ w_star - tv) / nv
+    return -2.0 * np.exp(lam) * w_star * np.linalg.solve(H, g), H, g
+
+
+def test_ridge_solution_is_stationary():
+    wl, prob, lam, w_star = ridge_setup()
+    _, grad = orc.lower_grad(prob, w_star, lam)
+    assert np.linalg.norm(grad) < 1e-12
+
+
+def test_ridge_truncated_neumann_closed_form():
+    """K products give K+1 series terms scaled by alpha: q_K = H^-1 (I - (I - aH)^(K+1)) g."""
+    wl, prob, lam, w_star = ridge_setup()
+    full, H, g = ridge_closed_form(wl, lam, w_star)
+    evals, Q = np.linalg.eigh(H)
+    for K, alpha in [(20, 0.05), (0, 0.05), (3, 0.2)]:
+        shrink = 1.0 - (1.0 - alpha * evals) ** (K + 1)
+        qK = Q @ ((shrink / evals) * (Q.T @ g))
+        expect = -2.0 * np.exp(lam) * w_star * qK
+        got = orc.hypergrad_neumann(prob, w_star, lam, K, alpha)
+        assert rel_l2(got, expect) < 1e-12
+    # K=20, alpha=0.05 is far from converged on this spectrum: the pin above is the
+    # truncated form, and the full closed form must differ visibly.
+    got = orc.hypergrad_neumann(prob, w_star, lam, 20, 0.05)
+    assert rel_l2(got, full) > 0.05
+
+
+def test_ridge_neumann_converges_to_closed_form():
+    wl, prob, lam, w_star = ridge_setup()
+    full, H, _ = ridge_closed_form(wl, lam, w_star)
+    alpha = 1.0 / np.linalg.eigvalsh(H).max()
+    got = orc.hypergrad_neumann(prob, w_star, lam, 400, alpha)
+    assert rel_l2(got, full) < 1e-9
+
+
+def test_ridge_closed_form_vs_fd_through_solver():
+    """True hypergradient by differencing L_val(w*(lambda)) through the exact solver."""
+    wl, prob, lam, w_star = ridge_setup()
+    full, _, _ = ridge_closed_form(wl, lam, w_star)
+    Xv = wl.X_val.astype(np.float64)
+    tv = wl.t_val.astype(np.float64).ravel()
+
+    def val_of(l):
+        ws = orc.ridge_solve(wl.X_tr, wl.t_tr, l)
+        r = Xv @ ws - tv
+        return (r * r).mean()
+
+    h = 1e-5
+    fd = np.zeros_like(lam)
+    for j in range(lam.size):
+        e = np.zeros_like(lam)
+        e[j] = h
+        fd[j] = (val_of(lam + e) - val_of(lam - e)) / (2 * h)
+    assert rel_l2(fd, full) < 1e-7
+
+
+def test_ridge_fd_equals_neumann_and_k0():
+    """Quadratic lower cost: central differences are exact, so the two variants agree."""
+    wl, prob, lam, w_star = ridge_setup()
+    a = orc.hypergrad_neumann(prob, w_star, lam, 20, 0.05)
+    b = orc.hypergrad_fd(prob, w_star, lam, 20, 0.05, 0.01)
+    assert rel_l2(b, a) < 1e-8
+    g = orc.upper_grad(prob, w_star)[1]
+    k0 = orc.hypergrad_fd(prob, w_star, lam, 0, 0.05, 0.01)
+    assert rel_l2(k0, -2.0 * np.exp(lam) * w_star * (0.05 * g)) < 1e-8
+
+
+# ---------------------------------------------------------------- costs and first-order gradients
+
+@pytest.mark.parametrize("cfg", TINY)
+def test_costs_and_gradients_vs_torch(cfg):
+    wl = wk.tiny(**cfg)
+    prob = oracle_problem(wl)
+    lower, upper = torch_costs(wl)
+    w = torch.tensor(wl.w, dtype=torch.float64, requires_grad=True)
+    lam = torch.tensor(wl.lam, dtype=torch.float64, requires_grad=True)
+    Ll = lower(w, lam)
+    gl, = torch.autograd.grad(Ll, w)
+    cost, grad = orc.lower_grad(prob, wl.w, wl.lam)
+    assert abs(cost - Ll.item()) < 1e-12 * max(1, abs(cost))
+    assert abs(orc.lower_cost(prob, wl.w, wl.lam) - Ll.item()) < 1e-12 * max(1, abs(cost))
+    assert rel_l2(grad, gl.numpy()) < 1e-12
+    Lu = upper(w)
+    gu, = torch.autograd.grad(Lu, w)
+    cu, gradu = orc.upper_grad(prob, wl.w)
+    assert abs(cu - Lu.item()) < 1e-12 * max(1, abs(cu))
+    assert rel_l2(gradu, gu.numpy()) < 1e-12
+
+
+@pytest.mark.parametrize("cfg", TINY)
+def test_lower_grad_vs_fd_of_cost(cfg):
+    """For the reweighting cost the weights are constants, so difference sum_i s_i l_i(w) with s frozen."""
+    wl = wk.tiny(**cfg)
+    prob = oracle_problem(wl)
+    w = wl.w.astype(np.float64)
+    lam = wl.lam.astype(np.float64)
+    if wl.hp == "reweight":
+        X, tgt = prob.batch("train")
+        ell0, _ = orc.sample_losses(prob, orc.forward(prob, w, X)[1][-1], tgt)
+        s = orc.sample_scales(prob, ell0, lam, True)
+
+        def cost(ww):
+            ell, _ = orc.sample_losses(prob, orc.forward(prob, ww, X)[1][-1], tgt)
+            return float((s * ell).sum())
+    else:
+        def cost(ww):
+            return orc.lower_cost(prob, ww, lam)
+    _, grad = orc.lower_grad(prob, w, lam)
+    h = 1e-6
+    fd = np.zeros_like(w)
+    for j in range(w.size):
+        e = np.zeros_like(w)
+        e[j] = h
+        fd[j] = (cost(w + e) - cost(w - e)) / (2 * h)
+    assert rel_l2(grad, fd) < 1e-7
+
+
+def test_gelu_derivatives_vs_fd():
+    z = np.linspace(-4, 4, 41)
+    h = 1e-5
+    f, d1, d2 = orc.activation(z, "gelu")
+    fp, dp, _ = orc.activation(z + h, "gelu")
+    fm, dm, _ = orc.activation(z - h, "gelu")
+    assert np.allclose(d1, (fp - fm) / (2 * h), atol=1e-9)
+    assert np.allclose(d2, (dp - dm) / (2 * h), atol=1e-9)
+    assert np.allclose(f, torch.nn.functional.gelu(torch.tensor(z)).numpy(), atol=1e-14)
+    r = orc.activation(np.array([-1.0, 0.0, 2.0]), "relu")
+    assert r[0].tolist() == [0.0, 0.0, 2.0] and r[1].tolist() == [0.0, 0.0, 1.0] and not r[2].any()
+
+
+# ---------------------------------------------------------------- P5/P6/P7/P11: Hessian-vector product
+
+@pytest.mark.parametrize("cfg", TINY)
+def test_hvp_vs_torch_double_backward(cfg):
+    wl = wk.tiny(**cfg)
+    prob = oracle_problem(wl)
+    lower, _ = torch_costs(wl)
+    w = torch.tensor(wl.w, dtype=torch.float64, requires_grad=True)
+    lam = torch.tensor(wl.lam, dtype=torch.float64)
+    v = _vec(3, wl.w.size)
+    g, = torch.autograd.grad(lower(w, lam), w, create_graph=True)
+    Hv, = torch.autograd.grad((g * torch.tensor(v)).sum(), w)
+    assert rel_l2(orc.hvp(prob, wl.w, wl.lam, v), Hv.numpy()) < 1e-11
+
+
+@pytest.mark.parametrize("cfg", TINY)
+def test_hvp_vs_fd_of_gradient_and_fd_variant(cfg):
+    wl = wk.tiny(**cfg)
+    prob = oracle_problem(wl)
+    w = wl.w.astype(np.float64)
+    v = _vec(4, w.size)
+    h = 1e-6
+    if wl.hp == "reweight":
+        # weights must stay frozen at l_i(w): difference the gradient with fixed scales
+        X, tgt = prob.batch("train")
+        a0, zs0 = orc.forward(prob, w, X)
+        ell0, _ = orc.sample_losses(prob, zs0[-1], tgt)
+        s = orc.sample_scales(prob, ell0, wl.lam, True)
+
+        def grad(ww):
+            a, zs = orc.forward(prob, ww, X)
+            _, dz = orc.sample_losses(prob, zs[-1], tgt)
+            return orc.backprop(prob, ww, a, zs, s[:, None] * dz)
+    else:
+        def grad(ww):
+            return orc.lower_grad(prob, ww, wl.lam)[1]
+    fd = (grad(w + h * v) - grad(w - h * v)) / (2 * h)
+    Hv = orc.hvp(prob, w, wl.lam, v)
+    assert rel_l2(Hv, fd) < 1e-7
+    if wl.hp == "l2":
+        # the finite-difference product of the method itself (step 0.01/||v||): close, not equal
+        # (a ReLU net is piecewise linear: a step that crosses a kink is not small, so the
+        # closeness check uses a shorter step there)
+        approx = orc.hvp_fd(prob, w, wl.lam, v, 0.01 if wl.act != "relu" else 1e-6)
+        assert rel_l2(approx, Hv) < 1e-3
+        approx = orc.hvp_fd(prob, w, wl.lam, v, 0.01)
+        # invariant to the scale of v up to rounding (eps ~ 1/||v||)
+        assert rel_l2(orc.hvp_fd(prob, w, wl.lam, 7.0 * v, 0.01), 7.0 * approx) < 1e-9
+    assert not orc.hvp_fd(prob, w, wl.lam, np.zeros_like(w), 0.01).any()
+
+
+@pytest.mark.parametrize("cfg", TINY)
+def test_hessian_symmetric_and_linear(cfg):
+    wl = wk.tiny(**cfg)
+    prob = oracle_problem(wl)
+    H = dense_hessian_by_hvp(prob, wl.w, wl.lam)
+    assert np.abs(H - H.T).max() < 1e-12 * max(1.0, np.abs(H).max())
+    u, v = _vec(5, wl.w.size), _vec(6, wl.w.size)
+    Hu, Hv = orc.hvp(prob, wl.w, wl.lam, u), orc.hvp(prob, wl.w, wl.lam, v)
+    assert abs(u @ Hv - v @ Hu) < 1e-11 * (1 + abs(u @ Hv))
+    assert rel_l2(orc.hvp(prob, wl.w, wl.lam, 2.5 * u - 0.5 * v), 2.5 * Hu - 0.5 * Hv) < 1e-12
+    assert rel_l2(H @ u, Hu) < 1e-12
+
+
+def test_softmax_regression_hessian_textbook():
+    """L = 1: H = (1/B) sum_i x_i x_i' (x) (diag p_i - p_i p_i') + 2 diag e^lam."""
+    wl = wk.tiny(kind="l2", act="none", loss="ce", dims=(5, 4), batch=11)
+    prob = oracle_problem(wl)
+    X = wl.X_tr.astype(np.float64)
+    B, n, C = X.shape[0], 5, 4
+    W = wl.w[:n * C].astype(np.float64).reshape(n, C)
+    b = wl.w[n * C:].astype(np.float64)
+    Z = X @ W + b
+    P = np.exp(Z - Z.max(1, keepdims=True))
+    P /= P.sum(1, keepdims=True)
+    Xa = np.hstack([X, np.ones((B, 1))])            # bias as an extra input row
+    Hfull = np.zeros(((n + 1) * C, (n + 1) * C))
+    for i in range(B):
+        S = np.diag(P[i]) - np.outer(P[i], P[i])
+        Hfull += np.kron(np.outer(Xa[i], Xa[i]), S) / B
+    # flat layout is [W (n x C row-major), b (C)] which equals rows of the augmented matrix
+    Hfull += 2.0 * np.diag(np.exp(wl.lam.astype(np.float64)))
+    H = dense_hessian_by_hvp(prob, wl.w, wl.lam)
+    assert np.abs(H - Hfull).max() < 1e-13
+
+
+# ---------------------------------------------------------------- P8/P9: mixed VJP
+
+@pytest.mark.parametrize("cfg", TINY)
+def test_mixed_vjp_vs_torch_and_fd(cfg):
+    wl = wk.tiny(**cfg)
+    prob = oracle_problem(wl)
+    lower, _ = torch_costs(wl)
+    w = torch.tensor(wl.w, dtype=torch.float64, requires_grad=True)
+    lam = torch.tensor(wl.lam, dtype=torch.float64, requires_grad=True)
+    q = _vec(7, wl.w.size)
+    g, = torch.autograd.grad(lower(w, lam), w, create_graph=True)
+    m, = torch.autograd.grad((g * torch.tensor(q)).sum(), lam)
+    got = orc.mixed_vjp(prob, wl.w, wl.lam, q)
+    assert rel_l2(got, -m.numpy()) < 1e-11
+    # central difference in lambda of <grad_w L_L, q>
+    lam0 = wl.lam.astype(np.float64)
+    h = 1e-6
+    fd = np.zeros_like(lam0)
+    for j in range(lam0.size):
+        e = np.zeros_like(lam0)
+        e[j] = h
+        fd[j] = (orc.lower_grad(prob, wl.w, lam0 + e)[1] @ q - orc.lower_grad(prob, wl.w, lam0 - e)[1] @ q) / (2 * h)
+    assert rel_l2(got, -fd) < 1e-6
+    # the method's own finite-difference mixed term converges to the analytic one
+    assert rel_l2(orc.mixed_vjp_fd(prob, wl.w, wl.lam, q, 0.01 if wl.act != "relu" else 1e-6), got) < 1e-3
+    if wl.hp == "l2":
+        assert rel_l2(got, -2 * np.exp(lam0) * wl.w.astype(np.float64) * q) < 1e-15
+
+
+def test_per_sample_directional_vs_fd():
+    wl = wk.tiny(kind="reweight", act="gelu", loss="ce")
+    prob = oracle_problem(wl)
+    w = wl.w.astype(np.float64)
+    q = _vec(8, w.size)
+    c, ell = orc.per_sample_directional(prob, w, q)
+    X, tgt = prob.batch("train")
+    h = 1e-6
+    lp, _ = orc.sample_losses(prob, orc.forward(prob, w + h * q, X)[1][-1], tgt)
+    lm, _ = orc.sample_losses(prob, orc.forward(prob, w - h * q, X)[1][-1], tgt)
+    assert np.allclose(c, (lp - lm) / (2 * h), rtol=1e-7, atol=1e-9)
+
+
+def test_weight_net_vjp_vs_torch():
+    rng = np.random.default_rng(9)
+    H = 6
+    theta = rng.standard_normal(3 * H + 1)
+    ell = rng.uniform(0, 3, 9)
+    c = rng.standard_normal(9)
+    th = torch.tensor(theta, requires_grad=True)
+    x = torch.tensor(ell).reshape(-1, 1)
+    out = torch.sigmoid(torch.relu(x * th[:H] + th[H:2 * H]) @ th[2 * H:3 * H] + th[3 * H])
+    assert np.allclose(out.detach().numpy(), orc.weight_net(ell, theta, H), atol=1e-15)
+    g, = torch.autograd.grad((out * torch.tensor(c)).sum(), th)
+    assert rel_l2(orc.weight_net_theta_vjp(ell, theta, H, c), g.numpy()) < 1e-13
+
+
+# ---------------------------------------------------------------- P3: whole hypergradient
+
+@pytest.mark.parametrize("cfg", [TINY[0], TINY[1], TINY[4]])
+def test_neumann_converges_to_dense_implicit_hypergradient(cfg):
+    """Drive a tiny problem to a lower minimum, then compare with
+    -M' H^-1 g assembled from torch autograd Hessians (dense solve)."""
+    wl = wk.tiny(**cfg)
+    if wl.hp == "l2":
+        wl.lam = (wl.lam + 2.0).astype(np.float32)      # stronger decay: well-conditioned minimum
+    prob = oracle_problem(wl)
+    lam = wl.lam.astype(np.float64)
+    w = wl.w.astype(np.float64)
+    if wl.hp == "l2":
+        for _ in range(3000):
+            w = w - 0.2 * orc.lower_grad(prob, w, lam)[1]
+        assert np.linalg.norm(orc.lower_grad(prob, w, lam)[1]) < 1e-8
+    lower, upper = torch_costs(wl)
+    wt = torch.tensor(w, requires_grad=True)
+    lt = torch.tensor(lam, requires_grad=True)
+    g, = torch.autograd.grad(lower(wt, lt), wt, create_graph=True)
+    rows_w, rows_l = [], []
+    for j in range(w.size):
+        hw, hl = torch.autograd.grad(g[j], (wt, lt), retain_graph=True)
+        rows_w.append(hw.numpy())
+        rows_l.append(hl.numpy())
+    Hd, Md = np.array(rows_w), np.array(rows_l)          # H (d x d), M[j,:] = d g_j / d lambda
+    gu, = torch.autograd.grad(upper(wt), wt)
+    evals = np.linalg.eigvalsh(Hd)
+    if evals.min() <= 1e-6:
+        # reweighting data term at an arbitrary w need not be positive definite: shift is not
+        # allowed, so only compare the truncated series there
+        K, alpha = 6, 0.3 / np.abs(evals).max()
+        A = np.eye(w.size) - alpha * Hd
+        S, P = np.zeros_like(Hd), np.eye(w.size)
+        for _ in range(K + 1):
+            S += P
+            P = P @ A
+        expect = -Md.T @ (alpha * S @ gu.numpy())
+        got = orc.hypergrad_neumann(prob, w, lam, K, alpha)
+        assert rel_l2(got, expect) < 1e-10
+        return
+    alpha = 1.0 / evals.max()
+    K = int(math.ceil(40.0 / (alpha * evals.min())))
+    expect = -Md.T @ np.linalg.solve(Hd, gu.numpy())
+    got = orc.hypergrad_neumann(prob, w, lam, K, alpha)
+    assert rel_l2(got, expect) < 1e-9
+    # finite-difference variant lands close to the same thing
+    gotfd = orc.hypergrad_fd(prob, w, lam, K, alpha, 0.01 if wl.act != "relu" else 1e-6)
+    assert rel_l2(gotfd, expect) < 1e-3
+
+
+@pytest.mark.parametrize("cfg", TINY)
+def test_truncated_series_against_dense_matrix_power_sum(cfg):
+    wl = wk.tiny(**cfg)
+    prob = oracle_problem(wl)
+    H = dense_hessian_by_hvp(prob, wl.w, wl.lam)
+    g = orc.upper_grad(prob, wl.w)[1]
+    K, alpha = 4, 0.07
+    A = np.eye(H.shape[0]) - alpha * H
+    S, P = np.zeros_like(H), np.eye(H.shape[0])
+    for _ in range(K + 1):
+        S += P
+        P = P @ A
+    q = alpha * S @ g
+    assert rel_l2(orc.hypergrad_neumann(prob, wl.w, wl.lam, K, alpha),
+                  orc.mixed_vjp(prob, wl.w, wl.lam, q)) < 1e-12
+    assert rel_l2(orc.hypergrad_neumann(prob, wl.w, wl.lam, 0, alpha),
+                  orc.mixed_vjp(prob, wl.w, wl.lam, alpha * g)) < 1e-14
+
+
+# ---------------------------------------------------------------- P12: integer work
+
+def test_label_noise_integer_rule():
+    rng = np.random.default_rng(0)
+    n = 20000
+    y = rng.integers(0, 10, n).astype(np.int32)
+    alt = rng.integers(0, 10, n).astype(np.int32)
+    words = rng.integers(0, 2 ** 32, n, dtype=np.uint64).astype(np.uint32)
+    for p in (0.0, 0.3, 0.4, 1.0):
+        out, mask = orc.apply_label_noise(y, words, alt, p)
+        T = int(p * 2 ** 32)
+        ref_mask = np.array([int(x) < T for x in words], dtype=np.uint8)
+        assert (mask == ref_mask).all()
+        assert (out == np.where(ref_mask == 1, alt, y)).all()
+        assert abs(mask.mean() - p) < 5 * math.sqrt(max(p * (1 - p), 1e-9) / n) + 1e-12
+    # boundary words
+    out, mask = orc.apply_label_noise(np.array([1, 1, 1], dtype=np.int32),
+                                      np.array([0, 1717986917, 1717986918], dtype=np.uint32),
+                                      np.array([7, 7, 7], dtype=np.int32), 0.4)
+    assert mask.tolist() == [1, 1, 0] and out.tolist() == [7, 7, 1]
+
+
+def test_workload_labels_follow_the_noise_rule():
+    wl = wk.config(3)
+    out, mask = orc.apply_label_noise(wl.y_clean, wl.noise_words, wl.noise_alt, wl.noise_p)
+    assert (out == wl.y_tr).all()
+    assert 0.25 < mask.mean() < 0.55
+    assert wl.d == 792586 and wk.config(2).d == 203530
