@@ -1,0 +1,181 @@
+/*
+ * betty_hip.h -- C ABI of the MI355X (gfx950) hypergradient library.
+ *
+ * The library computes the base operation of gradient-based multilevel
+ * optimisation stated in the paper's Sec. 3.2 (Eq. 3-4): given a lower problem
+ *     w*(lambda) = argmin_w L_L(w, lambda)
+ * and an upper cost L_U(w*), the product of the best-response Jacobian with the
+ * upper direct gradient (Eq. 1 with one lower problem),
+ *     dL_U/dlambda = - (d^2 L_L / dlambda dw) H^{-1} grad_w L_U ,  H = d^2 L_L / dw dw,
+ * evaluated right-to-left with matrix-vector products only (Sec. 3.2), by the
+ * approximate-implicit-differentiation variants the paper lists there: the Neumann
+ * series (AID-NMN) and finite differences (AID-FD).
+ *
+ * Model family: an MLP classifier/regressor with L linear layers
+ *     a_0 = X,  z_l = a_{l-1} W_l + b_l,  a_l = phi(z_l) (l < L),  output z_L,
+ * per-sample loss l_i (softmax cross-entropy on int labels, or squared error),
+ * lower cost either
+ *     BETTY_HP_L2_DECAY:      mean_i l_i + sum_j exp(lambda_j) w_j^2   (App. D.1 structure:
+ *                             one weight-decay hyperparameter per parameter), or
+ *     BETTY_HP_REWEIGHT_NET:  mean_i R(l_i; theta) l_i with R a 1-H-1 MLP (ReLU hidden,
+ *                             sigmoid output) fed the value of l_i as a constant
+ *                             (App. B Listing 3, App. C "Meta-Weight-Network"),
+ * and upper cost mean_i l_i on the validation batch (Listing 3, level 2).
+ *
+ * Conventions common to every call
+ *  - All data pointers are DEVICE pointers unless a comment says "host".
+ *  - Parameter-shaped vectors (w, v, q, Hv, grad, and lambda for L2 decay) are flat fp32:
+ *    [W_1 (n_0 x n_1, row-major), b_1 (n_1), ..., W_L, b_L]; biases absent if has_bias == 0.
+ *    For the weight net lambda = theta = [u1 (H), b1 (H), u2 (H), b2 (1)].
+ *  - X is row-major batch x n_0 fp32; labels are int32 in [0, n_L); targets are row-major
+ *    batch x n_L fp32.
+ *  - The caller owns every buffer, including the workspace.  The compute calls never
+ *    allocate or free device memory and never synchronise: work is enqueued on the bound
+ *    stream, outputs are valid once the caller has synchronised that stream.
+ *  - Outputs must not overlap inputs.  Pointers must be 4-byte aligned; the workspace 256-byte.
+ *  - Every call returns a betty_status; arguments are validated on the host before any
+ *    launch, so a failing call leaves its outputs untouched.  betty_last_error() returns
+ *    text for the most recent failure on that handle.
+ *  - Results are deterministic: identical inputs give bit-identical outputs.
+ *  - A handle is not thread-safe; use one handle per host thread/stream.
+ */
+#ifndef BETTY_HIP_H
+#define BETTY_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct betty_handle_s* betty_handle;
+
+typedef enum {
+  BETTY_OK = 0,
+  BETTY_EINVAL = -1,       /* bad scalar argument (K < 0, non-finite alpha, ...)        */
+  BETTY_ENULL = -2,        /* a required pointer is NULL                                */
+  BETTY_ESHAPE = -3,       /* inconsistent problem description                          */
+  BETTY_EWORKSPACE = -4,   /* workspace missing or too small / batches not set          */
+  BETTY_EALIGN = -5,       /* misaligned pointer                                        */
+  BETTY_EUNSUPPORTED = -6, /* combination not implemented                               */
+  BETTY_EDEVICE = -7       /* a HIP runtime call failed                                 */
+} betty_status;
+
+typedef enum { BETTY_ACT_NONE = 0, BETTY_ACT_RELU = 1, BETTY_ACT_GELU_ERF = 2 } betty_act;
+typedef enum { BETTY_LOSS_MSE = 0, BETTY_LOSS_SOFTMAX_CE = 1 } betty_loss;
+typedef enum { BETTY_HP_L2_DECAY = 0, BETTY_HP_REWEIGHT_NET = 1 } betty_hp;
+/* Arithmetic of the GEMMs: fp32 operands, or operands rounded to bf16 (round to nearest
+ * even) with fp32 accumulation.  Loss math, reductions and all parameter-shaped vectors
+ * are fp32 in both.  The finite-difference variant always uses fp32 operands. */
+typedef enum { BETTY_PREC_FP32 = 0, BETTY_PREC_BF16_FP32ACC = 1 } betty_prec;
+
+typedef struct {
+  int n_layers;        /* L >= 1 linear layers                                          */
+  const int* dims;     /* host, L+1 entries n_0..n_L, copied by betty_create            */
+  int has_bias;
+  betty_act act;
+  betty_loss loss;
+  betty_hp hp;
+  betty_prec prec;
+  int batch_train;     /* samples in the lower (train) batch                            */
+  int batch_val;       /* samples in the upper (validation) batch                       */
+  int wnet_hidden;     /* H of the 1-H-1 weight net (ignored for L2 decay)              */
+} betty_problem_desc;
+
+typedef struct {
+  const float* x;        /* batch x n_0                                                 */
+  const int32_t* y;      /* labels, required for BETTY_LOSS_SOFTMAX_CE, else NULL       */
+  const float* target;   /* batch x n_L, required for BETTY_LOSS_MSE, else NULL         */
+} betty_batch;
+
+/* ---- set-up ---------------------------------------------------------------------- */
+
+/* Validates the description and builds the host-side plan.  No device work. */
+betty_status betty_create(const betty_problem_desc* desc, betty_handle* out);
+void betty_destroy(betty_handle h);
+const char* betty_last_error(betty_handle h);   /* host string owned by the handle */
+
+/* Number of parameters d, and the length of lambda (d, or 3H+1). */
+size_t betty_num_params(betty_handle h);
+size_t betty_num_hyper(betty_handle h);
+
+/* Bytes of device workspace the handle needs. */
+size_t betty_workspace_bytes(betty_handle h);
+
+/* Binds a caller-owned device workspace and a HIP stream (hipStream_t passed as void*,
+ * NULL = the default stream).  Enqueues a zero-fill of the workspace on that stream. */
+betty_status betty_bind(betty_handle h, void* workspace, size_t bytes, void* hip_stream);
+
+/* Registers the train (lower) and validation (upper) batches and enqueues the conversion
+ * of X into the operand layouts of the workspace.  The label/target pointers are kept and
+ * read by later calls, so they must stay valid; x may be released after the stream has
+ * run past this call. */
+betty_status betty_set_batches(betty_handle h, betty_batch train, betty_batch val);
+
+/* ---- the hot path (Sec. 3.2) --------------------------------------------------- */
+
+/* grad_w L_L(w, lambda) on the train batch (the "direct gradient" of the lower cost, Eq. 1);
+ * loss_or_null receives L_L (1 float). */
+betty_status betty_lower_grad(betty_handle h, const float* w, const float* lambda,
+                              float* grad_w, float* loss_or_null);
+
+/* grad_w L_U(w) on the validation batch; loss_or_null receives L_U. */
+betty_status betty_upper_grad(betty_handle h, const float* w, float* grad_w, float* loss_or_null);
+
+/* Hv = (d^2 L_L / dw dw) v at (w, lambda): forward-over-reverse product, H never formed. */
+betty_status betty_hvp(betty_handle h, const float* w, const float* lambda, const float* v,
+                       float* Hv);
+
+/* out = - grad_lambda < grad_w L_L(w, lambda), q >   (q held constant), length of lambda. */
+betty_status betty_mixed_vjp(betty_handle h, const float* w, const float* lambda,
+                             const float* q, float* out);
+
+/* Neumann-series hypergradient (AID-NMN):
+ *   g = grad_w L_U(w); v = p = g; K times { v <- v - alpha H v; p <- p + v }; q = alpha p;
+ *   dlambda = betty_mixed_vjp(q).     K >= 0, alpha finite. */
+betty_status betty_hypergrad_neumann(betty_handle h, const float* w, const float* lambda, int K,
+                                     float alpha, float* dlambda);
+
+/* Finite-difference hypergradient (AID-FD): as above with
+ *   H v := [grad_w L_L(w + e v) - grad_w L_L(w - e v)] / (2 e),  e = eps_scale / ||v||_2,
+ * and the mixed term by the same central difference of grad_lambda L_L along q.  Only
+ * first-order gradients are evaluated; K = 0 gives q = alpha g.  fp32 operands throughout.
+ * BETTY_HP_REWEIGHT_NET is not implemented for this variant (BETTY_EUNSUPPORTED). */
+betty_status betty_hypergrad_fd(betty_handle h, const float* w, const float* lambda, int K,
+                                float alpha, float eps_scale, float* dlambda);
+
+/* Uniform label noise as integer work: T = floor(p * 2^32);
+ *   mask_i = words_i < T;  y_out_i = mask_i ? alt_i : y_i.   n >= 0 elements, p in [0, 1].
+ * mask_or_null receives 0/1 bytes.  Runs on the handle's stream. */
+betty_status betty_apply_label_noise(betty_handle h, const int32_t* y, const uint32_t* words,
+                                     const int32_t* alt, double p, int n, int32_t* y_out,
+                                     uint8_t* mask_or_null);
+
+/* ---- per-kernel timing (measurement aid) ---------------------------------------- */
+
+typedef struct {
+  int kind;          /* BETTY_K_* below                                                 */
+  float ms;          /* duration of this launch between two events on the stream        */
+  double flops;      /* algorithmic flops of this launch (GEMMs), else 0                */
+  double bytes;      /* algorithmic bytes of this launch (vector kernels), else 0       */
+} betty_profile_rec;
+
+enum {
+  BETTY_K_GEMM = 0, BETTY_K_EPILOGUE = 1, BETTY_K_LOSS = 2, BETTY_K_SHADOW = 3,
+  BETTY_K_VECTOR = 4, BETTY_K_REDUCE = 5, BETTY_K_WNET = 6, BETTY_K_OTHER = 7
+};
+
+/* While enabled, every kernel launch of the handle is bracketed by HIP events on the
+ * bound stream.  betty_profile_collect synchronises the stream, converts the events to
+ * durations and returns how many records are available; betty_profile_get copies record i.
+ * Enabling clears earlier records.  Timing this way perturbs the launch pipeline: use it
+ * for per-kernel durations only, never inside a throughput measurement. */
+betty_status betty_profile_enable(betty_handle h, int on);
+int betty_profile_collect(betty_handle h);
+betty_status betty_profile_get(betty_handle h, int i, betty_profile_rec* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BETTY_HIP_H */

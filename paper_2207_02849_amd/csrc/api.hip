@@ -1,0 +1,699 @@
+// Host side of libbetty_hip.so: handle, argument validation, workspace plan, and the launch
+// sequences of the five hot-path calls (paper Sec. 3.2; Neumann and finite-difference
+// approximate implicit differentiation followed by the mixed second-order VJP).
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <new>
+#include <cstring>
+
+#include "internal.h"
+
+using namespace betty;
+
+namespace betty {
+
+void Ctx::begin(int kind, double flops, double bytes) {
+  if (!profiling) return;
+  ProfRec r{};
+  r.kind = kind; r.flops = flops; r.bytes = bytes; r.ms = -1.f;
+  if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) { profiling = false; return; }
+  (void)hipEventRecord(r.e0, stream);
+  recs.push_back(r);
+}
+
+void Ctx::end() {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess && first_error == hipSuccess) first_error = e;
+  if (profiling && !recs.empty()) (void)hipEventRecord(recs.back().e1, stream);
+}
+
+}  // namespace betty
+
+namespace {
+
+struct LayerInfo {
+  int n_in, n_out, n_in_p, n_out_p;
+  size_t w_off, b_off;       // offsets (in floats) into a flat parameter vector
+};
+
+// Buffers that depend on which batch (train / validation) is being propagated.
+struct SideBuf {
+  int B = 0, Bp = 0;
+  size_t X = 0, XT = 0;                       // a_0 and its transpose
+  std::vector<size_t> A, At, D, Dt;           // a_l (1..L-1), delta_l (1..L), each in both orientations
+  std::vector<size_t> dphi, e2;               // fp32 phi'(z_l); phi''(z_l) then (delta W^T) phi''
+  size_t ZL = 0, P = 0, ell = 0, s = 0, omega = 0;
+};
+
+// One complete set of GEMM operands in a given element type.
+struct OperandSet {
+  Elem elem = ELEM_F32;
+  bool present = false;
+  SideBuf side[2];                            // 0 = train (lower), 1 = validation (upper)
+  std::vector<size_t> Wn, Wt, Vn, Vt;         // W_l as stored / transposed; same for the direction
+  std::vector<size_t> RA, RAt, RD, RDt, Rz;   // R-op quantities (train side only)
+  size_t cvec = 0;
+};
+
+}  // namespace
+
+struct betty_handle_s {
+  betty_problem_desc desc{};
+  std::vector<int> dims;
+  std::vector<LayerInfo> layers;
+  int L = 0;
+  size_t d = 0, n_hyper = 0;
+  int max_np = 0, max_Bp = 0;
+  std::string err;
+  Ctx ctx;
+  char* ws = nullptr;
+  size_t ws_need = 0;
+  bool bound = false, batches = false;
+  betty_batch batch[2]{};
+  OperandSet sets[2];        // [0]: element type of desc.prec; [1]: fp32 set for finite differences when prec is bf16
+  size_t scratch = 0;        // fp32 GEMM output / split-K partials
+  int s_max = 16;
+  size_t vec_g = 0, vec_v = 0, vec_p = 0, vec_Hv = 0, vec_wpm = 0, vec_Gm = 0;
+  size_t partials = 0, scalars = 0;
+
+  template <typename T = void> T* at(size_t off) const { return (T*)(ws + off); }
+  float* f(size_t off) const { return (float*)(ws + off); }
+};
+
+namespace {
+
+betty_status fail(betty_handle h, betty_status st, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (h) h->err = buf;
+  return st;
+}
+
+struct Planner {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    size_t o = off;
+    off += (bytes + 255) / 256 * 256;
+    return o;
+  }
+};
+
+void plan_side(betty_handle h, Planner& pl, SideBuf& sb, Elem elem, int B, bool lower) {
+  const int L = h->L;
+  const size_t es = elem_size(elem);
+  sb.B = B;
+  sb.Bp = padup(B);
+  const size_t Bp = sb.Bp;
+  sb.X = pl.take(Bp * h->layers[0].n_in_p * es);
+  sb.XT = pl.take((size_t)h->layers[0].n_in_p * Bp * es);
+  sb.A.assign(L + 1, 0); sb.At.assign(L + 1, 0); sb.D.assign(L + 1, 0); sb.Dt.assign(L + 1, 0);
+  sb.dphi.assign(L + 1, 0); sb.e2.assign(L + 1, 0);
+  for (int l = 1; l <= L; ++l) {
+    const size_t np = h->layers[l - 1].n_out_p;
+    if (l < L) {
+      sb.A[l] = pl.take(Bp * np * es);
+      sb.At[l] = pl.take(np * Bp * es);
+      sb.dphi[l] = pl.take(Bp * np * 4);
+      if (lower && h->desc.act == BETTY_ACT_GELU_ERF) sb.e2[l] = pl.take(Bp * np * 4);
+    }
+    sb.D[l] = pl.take(Bp * np * es);
+    sb.Dt[l] = pl.take(np * Bp * es);
+  }
+  const size_t Cp = h->layers[L - 1].n_out_p;
+  sb.ZL = pl.take(Bp * Cp * 4);
+  sb.P = pl.take(Bp * Cp * 4);
+  sb.ell = pl.take(Bp * 4);
+  sb.s = pl.take(Bp * 4);
+  sb.omega = pl.take(Bp * 4);
+}
+
+void plan_set(betty_handle h, Planner& pl, OperandSet& os, Elem elem) {
+  const int L = h->L;
+  const size_t es = elem_size(elem);
+  os.elem = elem;
+  os.present = true;
+  plan_side(h, pl, os.side[0], elem, h->desc.batch_train, true);
+  plan_side(h, pl, os.side[1], elem, h->desc.batch_val, false);
+  os.Wn.assign(L, 0); os.Wt.assign(L, 0); os.Vn.assign(L, 0); os.Vt.assign(L, 0);
+  for (int i = 0; i < L; ++i) {
+    const size_t m = (size_t)h->layers[i].n_in_p * h->layers[i].n_out_p * es;
+    os.Wn[i] = pl.take(m); os.Wt[i] = pl.take(m); os.Vn[i] = pl.take(m); os.Vt[i] = pl.take(m);
+  }
+  const size_t Bp = os.side[0].Bp;
+  os.RA.assign(L + 1, 0); os.RAt.assign(L + 1, 0); os.RD.assign(L + 1, 0); os.RDt.assign(L + 1, 0);
+  os.Rz.assign(L + 1, 0);
+  for (int l = 1; l <= L; ++l) {
+    const size_t np = h->layers[l - 1].n_out_p;
+    if (l < L) { os.RA[l] = pl.take(Bp * np * es); os.RAt[l] = pl.take(np * Bp * es); }
+    os.RD[l] = pl.take(Bp * np * es);
+    os.RDt[l] = pl.take(np * Bp * es);
+    os.Rz[l] = pl.take(Bp * np * 4);
+  }
+  os.cvec = pl.take(Bp * 4);
+}
+
+void plan(betty_handle h) {
+  Planner pl;
+  const Elem main_elem = h->desc.prec == BETTY_PREC_BF16_FP32ACC ? ELEM_BF16 : ELEM_F32;
+  plan_set(h, pl, h->sets[0], main_elem);
+  if (main_elem == ELEM_BF16) plan_set(h, pl, h->sets[1], ELEM_F32);
+  h->scratch = pl.take((size_t)h->s_max * h->max_Bp * h->max_np * 4);
+  const size_t vb = h->d * 4;
+  h->vec_g = pl.take(vb); h->vec_v = pl.take(vb); h->vec_p = pl.take(vb); h->vec_Hv = pl.take(vb);
+  h->vec_wpm = pl.take(vb); h->vec_Gm = pl.take(vb);
+  h->partials = pl.take(1024 * 8);
+  h->scalars = pl.take(256);
+  h->ws_need = pl.off;
+}
+
+OperandSet& fd_operands(betty_handle h) { return h->sets[1].present ? h->sets[1] : h->sets[0]; }
+
+int choose_splitk(betty_handle h, Elem elem, int Mp, int Np, int Ktot_p) {
+  const int tiles = (Mp / 128) * (Np / 128);
+  const int kt = elem == ELEM_BF16 ? 32 : 16;
+  const int TT = Ktot_p / kt;
+  int S = (256 + tiles - 1) / tiles;
+  if (S > h->s_max) S = h->s_max;
+  if (S > TT) S = TT;
+  if (S < 1) S = 1;
+  return S;
+}
+
+// fp32 GEMM into the scratch area (split-K partials), returns how to read it back
+SplitSrc gemm_to_scratch(betty_handle h, Elem elem, const void* A0, int lda0, const void* B0, int ldb0, int K0p,
+                         const void* A1, int lda1, const void* B1, int ldb1, int K1p, int M, int N,
+                         int Mp, int Np, double flops) {
+  GemmArgs g{};
+  g.A[0] = A0; g.B[0] = B0; g.lda[0] = lda0; g.ldb[0] = ldb0; g.Kp[0] = K0p;
+  g.A[1] = A1 ? A1 : A0; g.B[1] = B1 ? B1 : B0; g.lda[1] = lda1; g.ldb[1] = ldb1; g.Kp[1] = A1 ? K1p : 0;
+  g.C = h->f(h->scratch);
+  g.ldc = Np;
+  g.M = M; g.N = N; g.Mp = Mp; g.Np = Np;
+  g.splitk = choose_splitk(h, elem, Mp, Np, g.Kp[0] + g.Kp[1]);
+  g.split_stride = (long long)Mp * Np;
+  launch_gemm(h->ctx, elem, g, flops);
+  return SplitSrc{g.C, g.ldc, g.splitk, g.split_stride};
+}
+
+void gemm_to_flat(betty_handle h, Elem elem, const void* A0, int lda0, const void* B0, int ldb0, int K0p,
+                  const void* A1, int lda1, const void* B1, int ldb1, int K1p, int M, int N, int Mp,
+                  int Np, float* C, int ldc, double flops) {
+  GemmArgs g{};
+  g.A[0] = A0; g.B[0] = B0; g.lda[0] = lda0; g.ldb[0] = ldb0; g.Kp[0] = K0p;
+  g.A[1] = A1 ? A1 : A0; g.B[1] = B1 ? B1 : B0; g.lda[1] = lda1; g.ldb[1] = ldb1; g.Kp[1] = A1 ? K1p : 0;
+  g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.Mp = Mp; g.Np = Np; g.splitk = 1; g.split_stride = 0;
+  launch_gemm(h->ctx, elem, g, flops);
+}
+
+// operand copies of a flat parameter-shaped vector: per layer, as stored (n_in x n_out) and transposed
+void make_shadows(betty_handle h, OperandSet& os, const float* flat, float scale,
+                  std::vector<size_t>* N, std::vector<size_t>* T) {
+  for (int i = 0; i < h->L; ++i) {
+    const LayerInfo& li = h->layers[i];
+    launch_convert_dual(h->ctx, os.elem, flat + li.w_off, li.n_out, scale, li.n_in, li.n_out,
+                        N ? h->at<void>((*N)[i]) : nullptr, li.n_out_p, T ? h->at<void>((*T)[i]) : nullptr,
+                        li.n_in_p);
+  }
+}
+
+// A ReLU mask is a discontinuous function of the pre-activation: deciding it from bf16-rounded
+// operands flips about one unit in a thousand, which alone costs a few percent of relative error
+// in every gradient that passes through the mask.  With bf16 operands the forward products of a
+// ReLU network are therefore formed from the fp32 operand set; all other GEMMs stay bf16.
+bool hybrid_forward(betty_handle h, const OperandSet& os) {
+  return os.elem == ELEM_BF16 && h->desc.act == BETTY_ACT_RELU && h->sets[1].present;
+}
+
+// operand copies of the parameters w for everything that follows
+void make_weight_operands(betty_handle h, OperandSet& os, const float* w) {
+  make_shadows(h, os, w, 1.f, &os.Wn, &os.Wt);
+  if (hybrid_forward(h, os)) make_shadows(h, h->sets[1], w, 1.f, nullptr, &h->sets[1].Wt);
+}
+
+// a_l, phi'(z_l) (and phi'' on the lower side), logits, per-sample loss, output delta
+void forward_and_loss(betty_handle h, OperandSet& os, int side, const float* w, const float* theta) {
+  SideBuf& sb = os.side[side];
+  const int L = h->L, B = sb.B, Bp = sb.Bp;
+  const bool lower = side == 0;
+  const bool hybrid = hybrid_forward(h, os);
+  OperandSet& fs = hybrid ? h->sets[1] : os;          // operands of the forward products
+  SideBuf& fb = fs.side[side];
+  for (int l = 1; l <= L; ++l) {
+    const LayerInfo& li = h->layers[l - 1];
+    const void* Aop = l == 1 ? h->at<void>(fb.X) : h->at<void>(fb.A[l - 1]);
+    SplitSrc src = gemm_to_scratch(h, fs.elem, Aop, li.n_in_p, h->at<void>(fs.Wt[l - 1]), li.n_in_p, li.n_in_p,
+                                   nullptr, 0, nullptr, 0, 0, B, li.n_out, Bp, li.n_out_p,
+                                   2.0 * B * li.n_in * li.n_out);
+    const bool last = l == L;
+    launch_fwd_epilogue(h->ctx, fs.elem, src, h->desc.has_bias ? w + li.b_off : nullptr, h->desc.act, last,
+                        B, li.n_out, last ? h->f(sb.ZL) : nullptr, last ? nullptr : h->f(sb.dphi[l]),
+                        (!last && sb.e2[l]) ? h->f(sb.e2[l]) : nullptr, li.n_out_p,
+                        last ? nullptr : h->at<void>(fb.A[l]), li.n_out_p,
+                        (last || hybrid) ? nullptr : h->at<void>(fb.At[l]), Bp);
+    if (hybrid && !last)
+      launch_convert_dual(h->ctx, os.elem, h->f(fb.A[l]), li.n_out_p, 1.f, B, li.n_out, h->at<void>(sb.A[l]),
+                          li.n_out_p, h->at<void>(sb.At[l]), Bp);
+  }
+  const LayerInfo& lo = h->layers[L - 1];
+  LossArgs a{};
+  a.loss = h->desc.loss;
+  a.reweight = (lower && h->desc.hp == BETTY_HP_REWEIGHT_NET) ? 1 : 0;
+  a.hidden = h->desc.wnet_hidden;
+  a.Z = h->f(sb.ZL); a.ldz = lo.n_out_p;
+  a.y = h->batch[side].y; a.target = h->batch[side].target; a.C = lo.n_out;
+  a.theta = theta;
+  a.rows = B; a.inv_batch = 1.0f / (float)B;
+  a.ell = h->f(sb.ell); a.s = h->f(sb.s); a.omega = h->f(sb.omega);
+  a.P = h->f(sb.P);
+  a.dZ = h->f(h->scratch); a.lddz = lo.n_out_p;
+  launch_loss_rows(h->ctx, a);
+  launch_convert_dual(h->ctx, os.elem, a.dZ, a.lddz, 1.f, B, lo.n_out, h->at<void>(sb.D[L]), lo.n_out_p,
+                      h->at<void>(sb.Dt[L]), Bp);
+}
+
+// delta_l for every layer; parameter gradient into grad_or_null (data term only)
+void backward(betty_handle h, OperandSet& os, int side, float* grad_or_null) {
+  SideBuf& sb = os.side[side];
+  const int L = h->L, B = sb.B, Bp = sb.Bp;
+  for (int l = L; l >= 1; --l) {
+    const LayerInfo& li = h->layers[l - 1];
+    if (grad_or_null) {
+      const void* AT = l == 1 ? h->at<void>(sb.XT) : h->at<void>(sb.At[l - 1]);
+      gemm_to_flat(h, os.elem, AT, Bp, h->at<void>(sb.Dt[l]), Bp, Bp, nullptr, 0, nullptr, 0, 0,
+                   li.n_in, li.n_out, li.n_in_p, li.n_out_p, grad_or_null + li.w_off, li.n_out,
+                   2.0 * B * li.n_in * li.n_out);
+      if (h->desc.has_bias)
+        launch_row_sums(h->ctx, os.elem, h->at<void>(sb.Dt[l]), Bp, li.n_out, B, grad_or_null + li.b_off);
+    }
+    if (l > 1) {
+      SplitSrc src = gemm_to_scratch(h, os.elem, h->at<void>(sb.D[l]), li.n_out_p, h->at<void>(os.Wn[l - 1]),
+                                     li.n_out_p, li.n_out_p, nullptr, 0, nullptr, 0, 0, B, li.n_in, Bp,
+                                     li.n_in_p, 2.0 * B * li.n_in * li.n_out);
+      launch_bwd_epilogue(h->ctx, os.elem, src, h->f(sb.dphi[l - 1]),
+                          sb.e2[l - 1] ? h->f(sb.e2[l - 1]) : nullptr, li.n_in_p, B, li.n_in,
+                          h->at<void>(sb.D[l - 1]), li.n_in_p, h->at<void>(sb.Dt[l - 1]), Bp);
+    }
+  }
+}
+
+// R-forward along the direction whose operand copies are in os.Vn / os.Vt and whose fp32 flat
+// form is `vflat` (for the bias directions).  Leaves Rz_l (fp32) and Ra_l.
+void r_forward(betty_handle h, OperandSet& os, const float* vflat, float vscale) {
+  SideBuf& sb = os.side[0];
+  const int L = h->L, B = sb.B, Bp = sb.Bp;
+  (void)vscale;
+  for (int l = 1; l <= L; ++l) {
+    const LayerInfo& li = h->layers[l - 1];
+    const void* a_prev = l == 1 ? h->at<void>(sb.X) : h->at<void>(sb.A[l - 1]);
+    SplitSrc src;
+    if (l == 1) {
+      src = gemm_to_scratch(h, os.elem, a_prev, li.n_in_p, h->at<void>(os.Vt[0]), li.n_in_p, li.n_in_p,
+                            nullptr, 0, nullptr, 0, 0, B, li.n_out, Bp, li.n_out_p,
+                            2.0 * B * li.n_in * li.n_out);
+    } else {
+      src = gemm_to_scratch(h, os.elem, h->at<void>(os.RA[l - 1]), li.n_in_p, h->at<void>(os.Wt[l - 1]),
+                            li.n_in_p, li.n_in_p, a_prev, li.n_in_p, h->at<void>(os.Vt[l - 1]), li.n_in_p,
+                            li.n_in_p, B, li.n_out, Bp, li.n_out_p, 4.0 * B * li.n_in * li.n_out);
+    }
+    const bool last = l == L;
+    launch_rfwd_epilogue(h->ctx, os.elem, src, h->desc.has_bias ? vflat + li.b_off : nullptr, last,
+                         last ? nullptr : h->f(sb.dphi[l]), h->f(os.Rz[l]), li.n_out_p, B, li.n_out,
+                         last ? nullptr : h->at<void>(os.RA[l]), li.n_out_p,
+                         last ? nullptr : h->at<void>(os.RAt[l]), Bp);
+  }
+}
+
+// Hv (data term) with the forward/backward cache of the train batch in place
+void hvp_cached(betty_handle h, OperandSet& os, const float* vflat, float* Hv) {
+  SideBuf& sb = os.side[0];
+  const int L = h->L, B = sb.B, Bp = sb.Bp;
+  r_forward(h, os, vflat, 1.f);
+  const LayerInfo& lo = h->layers[L - 1];
+  launch_loss_hessian_rows(h->ctx, h->desc.loss, h->f(sb.P), h->f(os.Rz[L]), lo.n_out_p, h->f(sb.s), B,
+                           lo.n_out, h->f(h->scratch), lo.n_out_p);
+  launch_convert_dual(h->ctx, os.elem, h->f(h->scratch), lo.n_out_p, 1.f, B, lo.n_out,
+                      h->at<void>(os.RD[L]), lo.n_out_p, h->at<void>(os.RDt[L]), Bp);
+  for (int l = L; l >= 1; --l) {
+    const LayerInfo& li = h->layers[l - 1];
+    const void* aT = l == 1 ? h->at<void>(sb.XT) : h->at<void>(sb.At[l - 1]);
+    if (l == 1) {
+      gemm_to_flat(h, os.elem, aT, Bp, h->at<void>(os.RDt[l]), Bp, Bp, nullptr, 0, nullptr, 0, 0, li.n_in,
+                   li.n_out, li.n_in_p, li.n_out_p, Hv + li.w_off, li.n_out, 2.0 * B * li.n_in * li.n_out);
+    } else {
+      gemm_to_flat(h, os.elem, h->at<void>(os.RAt[l - 1]), Bp, h->at<void>(sb.Dt[l]), Bp, Bp, aT, Bp,
+                   h->at<void>(os.RDt[l]), Bp, Bp, li.n_in, li.n_out, li.n_in_p, li.n_out_p,
+                   Hv + li.w_off, li.n_out, 4.0 * B * li.n_in * li.n_out);
+    }
+    if (h->desc.has_bias)
+      launch_row_sums(h->ctx, os.elem, h->at<void>(os.RDt[l]), Bp, li.n_out, B, Hv + li.b_off);
+    if (l > 1) {
+      SplitSrc src = gemm_to_scratch(h, os.elem, h->at<void>(os.RD[l]), li.n_out_p, h->at<void>(os.Wn[l - 1]),
+                                     li.n_out_p, li.n_out_p, h->at<void>(sb.D[l]), li.n_out_p,
+                                     h->at<void>(os.Vn[l - 1]), li.n_out_p, li.n_out_p, B, li.n_in, Bp,
+                                     li.n_in_p, 4.0 * B * li.n_in * li.n_out);
+      launch_rbwd_epilogue(h->ctx, os.elem, src, h->f(sb.dphi[l - 1]),
+                           sb.e2[l - 1] ? h->f(sb.e2[l - 1]) : nullptr, h->f(os.Rz[l - 1]), li.n_in_p, B,
+                           li.n_in, h->at<void>(os.RD[l - 1]), li.n_in_p, h->at<void>(os.RDt[l - 1]), Bp);
+    }
+  }
+}
+
+// full first-order gradient of the lower cost at w (operand copies of w already made)
+void lower_grad_seq(betty_handle h, OperandSet& os, const float* w, const float* lam, float* grad,
+                    float* loss_or_null) {
+  const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
+  forward_and_loss(h, os, 0, w, l2 ? nullptr : lam);
+  backward(h, os, 0, grad);
+  if (l2) launch_add_l2_term(h->ctx, grad, lam, w, h->d);
+  if (loss_or_null) {
+    float* add = nullptr;
+    if (l2) {
+      add = h->f(h->scalars) + 8;
+      launch_l2_cost(h->ctx, lam, w, h->d, h->at<double>(h->partials), add);
+    }
+    launch_weighted_loss_sum(h->ctx, h->f(os.side[0].s), h->f(os.side[0].ell), os.side[0].B, add, loss_or_null);
+  }
+}
+
+void upper_grad_seq(betty_handle h, OperandSet& os, const float* w, float* grad, float* loss_or_null) {
+  forward_and_loss(h, os, 1, w, nullptr);
+  backward(h, os, 1, grad);
+  if (loss_or_null)
+    launch_weighted_loss_sum(h->ctx, h->f(os.side[1].s), h->f(os.side[1].ell), os.side[1].B, nullptr, loss_or_null);
+}
+
+// forward/backward cache of the train batch for the R-op passes (no parameter gradient)
+void prepare_lower(betty_handle h, OperandSet& os, const float* w, const float* lam) {
+  forward_and_loss(h, os, 0, w, h->desc.hp == BETTY_HP_L2_DECAY ? nullptr : lam);
+  backward(h, os, 0, nullptr);
+}
+
+// out = -(1/B) sum_i c_i dR/dtheta with c_i = <grad_w l_i, scale * qflat>
+void mixed_reweight_seq(betty_handle h, OperandSet& os, const float* lam, const float* qflat, float scale,
+                        float* out) {
+  SideBuf& sb = os.side[0];
+  const int L = h->L;
+  const LayerInfo& lo = h->layers[L - 1];
+  // the direction is scale * qflat: scale once into a flat fp32 copy (its bias slices feed the
+  // R-forward epilogues), then make the operand copies from that
+  const float* qs = qflat;
+  if (scale != 1.f) {
+    float* tmp = h->f(h->vec_wpm);
+    launch_scale_copy(h->ctx, qflat, scale, tmp, h->d);
+    qs = tmp;
+  }
+  make_shadows(h, os, qs, 1.f, &os.Vn, &os.Vt);
+  r_forward(h, os, qs, 1.f);
+  launch_loss_directional_rows(h->ctx, h->desc.loss, h->f(sb.P), h->f(sb.ZL), h->batch[0].y,
+                               h->batch[0].target, h->f(os.Rz[L]), lo.n_out_p, sb.B, lo.n_out, h->f(os.cvec));
+  launch_wnet_theta_vjp(h->ctx, h->f(sb.ell), h->f(sb.omega), h->f(os.cvec), lam, h->desc.wnet_hidden, sb.B,
+                        1.0f / (float)sb.B, out);
+}
+
+bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+  const char* x = (const char*)a;
+  const char* y = (const char*)b;
+  return x < y + nb && y < x + na;
+}
+
+betty_status check_vec(betty_handle h, const void* p, const char* name) {
+  if (!p) return fail(h, BETTY_ENULL, "%s is NULL", name);
+  if (((uintptr_t)p) & 3) return fail(h, BETTY_EALIGN, "%s is not 4-byte aligned", name);
+  return BETTY_OK;
+}
+
+betty_status check_ready(betty_handle h) {
+  if (!h) return BETTY_ENULL;
+  if (!h->bound) return fail(h, BETTY_EWORKSPACE, "no workspace bound (call betty_bind)");
+  if (!h->batches) return fail(h, BETTY_EWORKSPACE, "batches not set (call betty_set_batches)");
+  return BETTY_OK;
+}
+
+betty_status finish(betty_handle h) {
+  if (h->ctx.first_error != hipSuccess) {
+    betty_status st = fail(h, BETTY_EDEVICE, "HIP error: %s", hipGetErrorString(h->ctx.first_error));
+    h->ctx.first_error = hipSuccess;
+    return st;
+  }
+  return BETTY_OK;
+}
+
+#define CHECK(expr) do { betty_status st__ = (expr); if (st__ != BETTY_OK) return st__; } while (0)
+
+}  // namespace
+
+extern "C" {
+
+betty_status betty_create(const betty_problem_desc* desc, betty_handle* out) {
+  if (!desc || !out) return BETTY_ENULL;
+  *out = nullptr;
+  if (!desc->dims) return BETTY_ENULL;
+  if (desc->n_layers < 1 || desc->n_layers > 64) return BETTY_ESHAPE;
+  for (int i = 0; i <= desc->n_layers; ++i)
+    if (desc->dims[i] < 1 || desc->dims[i] > (1 << 20)) return BETTY_ESHAPE;
+  if (desc->batch_train < 1 || desc->batch_val < 1 || desc->batch_train > (1 << 20) || desc->batch_val > (1 << 20))
+    return BETTY_ESHAPE;
+  if (desc->act < BETTY_ACT_NONE || desc->act > BETTY_ACT_GELU_ERF) return BETTY_EINVAL;
+  if (desc->loss != BETTY_LOSS_MSE && desc->loss != BETTY_LOSS_SOFTMAX_CE) return BETTY_EINVAL;
+  if (desc->hp != BETTY_HP_L2_DECAY && desc->hp != BETTY_HP_REWEIGHT_NET) return BETTY_EINVAL;
+  if (desc->prec != BETTY_PREC_FP32 && desc->prec != BETTY_PREC_BF16_FP32ACC) return BETTY_EINVAL;
+  if (desc->hp == BETTY_HP_REWEIGHT_NET && (desc->wnet_hidden < 1 || desc->wnet_hidden > 65536)) return BETTY_ESHAPE;
+
+  betty_handle h = new (std::nothrow) betty_handle_s();
+  if (!h) return BETTY_EDEVICE;
+  h->desc = *desc;
+  h->dims.assign(desc->dims, desc->dims + desc->n_layers + 1);
+  h->desc.dims = h->dims.data();
+  h->L = desc->n_layers;
+  size_t off = 0;
+  for (int l = 0; l < h->L; ++l) {
+    LayerInfo li{};
+    li.n_in = h->dims[l]; li.n_out = h->dims[l + 1];
+    li.n_in_p = padup(li.n_in); li.n_out_p = padup(li.n_out);
+    li.w_off = off; off += (size_t)li.n_in * li.n_out;
+    li.b_off = off;
+    if (desc->has_bias) off += li.n_out;
+    h->layers.push_back(li);
+    h->max_np = std::max(h->max_np, std::max(li.n_in_p, li.n_out_p));
+  }
+  h->d = off;
+  h->n_hyper = desc->hp == BETTY_HP_L2_DECAY ? h->d : (size_t)3 * desc->wnet_hidden + 1;
+  h->max_Bp = std::max(padup(desc->batch_train), padup(desc->batch_val));
+  plan(h);
+  *out = h;
+  return BETTY_OK;
+}
+
+void betty_destroy(betty_handle h) {
+  if (!h) return;
+  for (auto& r : h->ctx.recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+  delete h;
+}
+
+const char* betty_last_error(betty_handle h) { return h ? h->err.c_str() : "null handle"; }
+size_t betty_num_params(betty_handle h) { return h ? h->d : 0; }
+size_t betty_num_hyper(betty_handle h) { return h ? h->n_hyper : 0; }
+size_t betty_workspace_bytes(betty_handle h) { return h ? h->ws_need : 0; }
+
+betty_status betty_bind(betty_handle h, void* workspace, size_t bytes, void* hip_stream) {
+  if (!h) return BETTY_ENULL;
+  if (!workspace) return fail(h, BETTY_ENULL, "workspace is NULL");
+  if (((uintptr_t)workspace) & 255) return fail(h, BETTY_EALIGN, "workspace is not 256-byte aligned");
+  if (bytes < h->ws_need) return fail(h, BETTY_EWORKSPACE, "workspace has %zu bytes, %zu needed", bytes, h->ws_need);
+  h->ws = (char*)workspace;
+  h->ctx.stream = (hipStream_t)hip_stream;
+  h->bound = true;
+  h->batches = false;
+  launch_fill_zero(h->ctx, h->ws, h->ws_need);
+  return finish(h);
+}
+
+betty_status betty_set_batches(betty_handle h, betty_batch train, betty_batch val) {
+  if (!h) return BETTY_ENULL;
+  if (!h->bound) return fail(h, BETTY_EWORKSPACE, "no workspace bound (call betty_bind)");
+  const betty_batch b[2] = {train, val};
+  for (int s = 0; s < 2; ++s) {
+    CHECK(check_vec(h, b[s].x, s ? "val.x" : "train.x"));
+    if (h->desc.loss == BETTY_LOSS_SOFTMAX_CE) CHECK(check_vec(h, b[s].y, s ? "val.y" : "train.y"));
+    else CHECK(check_vec(h, b[s].target, s ? "val.target" : "train.target"));
+  }
+  h->batch[0] = train;
+  h->batch[1] = val;
+  const LayerInfo& l0 = h->layers[0];
+  for (int k = 0; k < 2; ++k) {
+    OperandSet& os = h->sets[k];
+    if (!os.present) continue;
+    for (int s = 0; s < 2; ++s) {
+      SideBuf& sb = os.side[s];
+      launch_convert_dual(h->ctx, os.elem, b[s].x, l0.n_in, 1.f, sb.B, l0.n_in, h->at<void>(sb.X), l0.n_in_p,
+                          h->at<void>(sb.XT), sb.Bp);
+    }
+  }
+  h->batches = true;
+  return finish(h);
+}
+
+betty_status betty_lower_grad(betty_handle h, const float* w, const float* lambda, float* grad_w,
+                              float* loss_or_null) {
+  CHECK(check_ready(h));
+  CHECK(check_vec(h, w, "w")); CHECK(check_vec(h, lambda, "lambda")); CHECK(check_vec(h, grad_w, "grad_w"));
+  if (loss_or_null) CHECK(check_vec(h, loss_or_null, "loss"));
+  if (overlaps(grad_w, h->d * 4, w, h->d * 4) || overlaps(grad_w, h->d * 4, lambda, h->n_hyper * 4))
+    return fail(h, BETTY_EINVAL, "grad_w overlaps an input");
+  OperandSet& os = h->sets[0];
+  make_weight_operands(h, os, w);
+  lower_grad_seq(h, os, w, lambda, grad_w, loss_or_null);
+  return finish(h);
+}
+
+betty_status betty_upper_grad(betty_handle h, const float* w, float* grad_w, float* loss_or_null) {
+  CHECK(check_ready(h));
+  CHECK(check_vec(h, w, "w")); CHECK(check_vec(h, grad_w, "grad_w"));
+  if (loss_or_null) CHECK(check_vec(h, loss_or_null, "loss"));
+  if (overlaps(grad_w, h->d * 4, w, h->d * 4)) return fail(h, BETTY_EINVAL, "grad_w overlaps w");
+  OperandSet& os = h->sets[0];
+  make_weight_operands(h, os, w);
+  upper_grad_seq(h, os, w, grad_w, loss_or_null);
+  return finish(h);
+}
+
+betty_status betty_hvp(betty_handle h, const float* w, const float* lambda, const float* v, float* Hv) {
+  CHECK(check_ready(h));
+  CHECK(check_vec(h, w, "w")); CHECK(check_vec(h, lambda, "lambda")); CHECK(check_vec(h, v, "v"));
+  CHECK(check_vec(h, Hv, "Hv"));
+  if (overlaps(Hv, h->d * 4, w, h->d * 4) || overlaps(Hv, h->d * 4, v, h->d * 4) ||
+      overlaps(Hv, h->d * 4, lambda, h->n_hyper * 4))
+    return fail(h, BETTY_EINVAL, "Hv overlaps an input");
+  OperandSet& os = h->sets[0];
+  make_weight_operands(h, os, w);
+  prepare_lower(h, os, w, lambda);
+  make_shadows(h, os, v, 1.f, &os.Vn, &os.Vt);
+  hvp_cached(h, os, v, Hv);
+  if (h->desc.hp == BETTY_HP_L2_DECAY) launch_add_l2_term(h->ctx, Hv, lambda, v, h->d);
+  return finish(h);
+}
+
+betty_status betty_mixed_vjp(betty_handle h, const float* w, const float* lambda, const float* q, float* out) {
+  CHECK(check_ready(h));
+  CHECK(check_vec(h, w, "w")); CHECK(check_vec(h, lambda, "lambda")); CHECK(check_vec(h, q, "q"));
+  CHECK(check_vec(h, out, "out"));
+  if (overlaps(out, h->n_hyper * 4, w, h->d * 4) || overlaps(out, h->n_hyper * 4, q, h->d * 4) ||
+      overlaps(out, h->n_hyper * 4, lambda, h->n_hyper * 4))
+    return fail(h, BETTY_EINVAL, "out overlaps an input");
+  if (h->desc.hp == BETTY_HP_L2_DECAY) {
+    launch_mixed_l2(h->ctx, lambda, w, q, 1.f, out, h->d);
+    return finish(h);
+  }
+  OperandSet& os = h->sets[0];
+  make_weight_operands(h, os, w);
+  forward_and_loss(h, os, 0, w, lambda);
+  mixed_reweight_seq(h, os, lambda, q, 1.f, out);
+  return finish(h);
+}
+
+static betty_status check_hyper_args(betty_handle h, const float* w, const float* lambda, int K, float alpha,
+                                     float* dlambda) {
+  CHECK(check_ready(h));
+  CHECK(check_vec(h, w, "w")); CHECK(check_vec(h, lambda, "lambda")); CHECK(check_vec(h, dlambda, "dlambda"));
+  if (K < 0) return fail(h, BETTY_EINVAL, "K must be >= 0 (got %d)", K);
+  if (!std::isfinite(alpha)) return fail(h, BETTY_EINVAL, "alpha must be finite");
+  if (overlaps(dlambda, h->n_hyper * 4, w, h->d * 4) || overlaps(dlambda, h->n_hyper * 4, lambda, h->n_hyper * 4))
+    return fail(h, BETTY_EINVAL, "dlambda overlaps an input");
+  return BETTY_OK;
+}
+
+betty_status betty_hypergrad_neumann(betty_handle h, const float* w, const float* lambda, int K, float alpha,
+                                     float* dlambda) {
+  CHECK(check_hyper_args(h, w, lambda, K, alpha, dlambda));
+  OperandSet& os = h->sets[0];
+  const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
+  float* g = h->f(h->vec_g); float* v = h->f(h->vec_v); float* p = h->f(h->vec_p); float* Hv = h->f(h->vec_Hv);
+  make_weight_operands(h, os, w);
+  upper_grad_seq(h, os, w, g, nullptr);
+  if (K > 0 || !l2) prepare_lower(h, os, w, lambda);
+  launch_copy2(h->ctx, g, v, p, h->d);
+  for (int k = 0; k < K; ++k) {
+    make_shadows(h, os, v, 1.f, &os.Vn, &os.Vt);
+    hvp_cached(h, os, v, Hv);
+    if (l2) launch_add_l2_term(h->ctx, Hv, lambda, v, h->d);
+    launch_neumann_update(h->ctx, v, p, Hv, alpha, h->d);
+  }
+  if (l2) launch_mixed_l2(h->ctx, lambda, w, p, alpha, dlambda, h->d);
+  else mixed_reweight_seq(h, os, lambda, p, alpha, dlambda);
+  return finish(h);
+}
+
+betty_status betty_hypergrad_fd(betty_handle h, const float* w, const float* lambda, int K, float alpha,
+                                float eps_scale, float* dlambda) {
+  CHECK(check_hyper_args(h, w, lambda, K, alpha, dlambda));
+  if (!std::isfinite(eps_scale) || eps_scale <= 0.f) return fail(h, BETTY_EINVAL, "eps_scale must be positive and finite");
+  if (h->desc.hp != BETTY_HP_L2_DECAY)
+    return fail(h, BETTY_EUNSUPPORTED, "finite-difference variant is implemented for L2-decay hyperparameters only");
+  OperandSet& os = fd_operands(h);
+  float* g = h->f(h->vec_g); float* v = h->f(h->vec_v); float* p = h->f(h->vec_p); float* Gp = h->f(h->vec_Hv);
+  float* Gm = h->f(h->vec_Gm); float* wpm = h->f(h->vec_wpm);
+  float* nrm2 = h->f(h->scalars); float* eps = h->f(h->scalars) + 1;
+  make_weight_operands(h, os, w);
+  upper_grad_seq(h, os, w, g, nullptr);
+  launch_copy2(h->ctx, g, v, p, h->d);
+  for (int k = 0; k < K; ++k) {
+    launch_sumsq(h->ctx, v, h->d, h->at<double>(h->partials), nrm2);
+    launch_fd_eps(h->ctx, nrm2, eps_scale, 1.f, eps);
+    launch_fd_perturb(h->ctx, w, v, eps, +1.f, wpm, h->d);
+    make_weight_operands(h, os, wpm);
+    lower_grad_seq(h, os, wpm, lambda, Gp, nullptr);
+    launch_fd_perturb(h->ctx, w, v, eps, -1.f, wpm, h->d);
+    make_weight_operands(h, os, wpm);
+    lower_grad_seq(h, os, wpm, lambda, Gm, nullptr);
+    launch_fd_update(h->ctx, v, p, Gp, Gm, eps, alpha, h->d);
+  }
+  launch_sumsq(h->ctx, p, h->d, h->at<double>(h->partials), nrm2);
+  launch_fd_eps(h->ctx, nrm2, eps_scale, alpha, eps);
+  launch_mixed_l2_fd(h->ctx, lambda, w, p, alpha, eps, dlambda, h->d);
+  return finish(h);
+}
+
+betty_status betty_apply_label_noise(betty_handle h, const int32_t* y, const uint32_t* words, const int32_t* alt,
+                                     double p, int n, int32_t* y_out, uint8_t* mask_or_null) {
+  if (!h) return BETTY_ENULL;
+  if (n < 0) return fail(h, BETTY_EINVAL, "n must be >= 0");
+  if (!(p >= 0.0 && p <= 1.0)) return fail(h, BETTY_EINVAL, "p must lie in [0, 1]");
+  if (n == 0) return BETTY_OK;
+  CHECK(check_vec(h, y, "y")); CHECK(check_vec(h, words, "words")); CHECK(check_vec(h, alt, "alt"));
+  CHECK(check_vec(h, y_out, "y_out"));
+  unsigned long long T = (unsigned long long)std::floor(p * 4294967296.0);
+  if (T > 4294967296ULL) T = 4294967296ULL;
+  launch_label_noise(h->ctx, y, words, alt, T, n, y_out, mask_or_null);
+  return finish(h);
+}
+
+betty_status betty_profile_enable(betty_handle h, int on) {
+  if (!h) return BETTY_ENULL;
+  for (auto& r : h->ctx.recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+  h->ctx.recs.clear();
+  h->ctx.profiling = on != 0;
+  return BETTY_OK;
+}
+
+int betty_profile_collect(betty_handle h) {
+  if (!h) return 0;
+  if (hipStreamSynchronize(h->ctx.stream) != hipSuccess) return 0;
+  for (auto& r : h->ctx.recs)
+    if (r.ms < 0.f && hipEventElapsedTime(&r.ms, r.e0, r.e1) != hipSuccess) r.ms = -1.f;
+  return (int)h->ctx.recs.size();
+}
+
+betty_status betty_profile_get(betty_handle h, int i, betty_profile_rec* out) {
+  if (!h || !out) return BETTY_ENULL;
+  if (i < 0 || i >= (int)h->ctx.recs.size()) return fail(h, BETTY_EINVAL, "profile record %d out of range", i);
+  const ProfRec& r = h->ctx.recs[i];
+  out->kind = r.kind; out->ms = r.ms; out->flops = r.flops; out->bytes = r.bytes;
+  return BETTY_OK;
+}
+
+}  // extern "C"
