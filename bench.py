@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Throughput of the hypergradient hot path on one MI355X.
+
+A step is one whole Neumann hypergradient (upper gradient on the validation batch,
+forward/backward cache on the train batch, K Hessian-vector products with the
+recurrence v <- v - alpha H v, and the mixed second-order VJP into lambda) of the
+metric workload: per-parameter L2-decay hyperparameters on the 4-linear-layer GELU MLP
+3072-1024-1024-1024-10 (d = 5 256 202), bf16 GEMM operands with fp32 accumulation,
+train/val batches of 256, K = 5, alpha = 0.01.  Inputs are synthetic (seeded Gaussian
+mixture) and resident in HBM before the timed region.
+
+Prints one JSON line.  Besides the contract keys it carries
+  roofline      the dominant kernel (the MFMA GEMM) against the bf16 MFMA peak,
+                from HIP events recorded by the library around every launch
+  cpu_baseline  the fp64 numpy oracle timed on the host cores for the same workload
+and, for context, the finite-difference variant's rate and the per-HVP figures.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0
+PEAK_HBM_GBS = 8000.0
+
+
+def algorithmic_flops(dims, B):
+    """grad = 6 B sum(P) - 2 B n0 n1; HVP = 12 B sum(P) - 8 B n0 n1 (weight matrices only)."""
+    P = sum(dims[i] * dims[i + 1] for i in range(len(dims) - 1))
+    first = dims[0] * dims[1]
+    return 6.0 * B * P - 2.0 * B * first, 12.0 * B * P - 8.0 * B * first
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=4, help="workload index (4 = the metric workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives or sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2207_02849_amd import binding
+    from paper_2207_02849_amd import workloads as wk
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    wl = wk.config(args.config)
+    b = binding.from_workload(wl, device="cuda:0")
+    w, lam = torch.as_tensor(wl.w).cuda(), torch.as_tensor(wl.lam).cuda()
+    out = torch.empty(b.n_hyper, dtype=torch.float32, device="cuda")
+    K, alpha = wl.K, wl.alpha
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    t_step = timed(lambda: b.betty_hypergrad_neumann(w, lam, K, alpha, out=out), args.steps, args.warmup)
+    n_side = max(10, args.steps // 4)
+    t_k0 = timed(lambda: b.betty_hypergrad_neumann(w, lam, 0, alpha, out=out), n_side, 5)
+    t_fd = None
+    if wl.hp == "l2":
+        t_fd = timed(lambda: b.betty_hypergrad_fd(w, lam, K, alpha, wl.eps_scale, out=out), n_side, 5)
+
+    B = wl.X_tr.shape[0]
+    grad_flops, hvp_flops = algorithmic_flops(wl.dims, B)
+    t_hvp = (t_step - t_k0) / K if K > 0 else float("nan")
+
+    # per-kernel durations from HIP events around every launch of a few extra steps
+    b.profile(True)
+    n_prof = 5
+    for _ in range(n_prof):
+        b.betty_hypergrad_neumann(w, lam, K, alpha, out=out)
+    recs = b.profile_records()
+    b.profile(False)
+    by_kind = {}
+    for kind, ms, flops, nbytes in recs:
+        a = by_kind.setdefault(kind, [0, 0.0, 0.0, 0.0])
+        a[0] += 1; a[1] += ms; a[2] += flops; a[3] += nbytes
+    gemm = by_kind.get("gemm", [1, 1.0, 0.0, 0.0])
+    gemm_tflops = gemm[2] / (gemm[1] * 1e-3) / 1e12
+    vec = by_kind.get("vector", [1, 1.0, 0.0, 0.0])
+    vec_gbs = vec[3] / (vec[1] * 1e-3) / 1e9
+    phases = {k: {"launches_per_step": v[0] / n_prof, "ms_per_step": v[1] / n_prof} for k, v in by_kind.items()}
+
+    result = {
+        "metric": "hypergradients/s, MLP Neumann K=5; HVP % of MFMA peak",
+        "value": 1.0 / t_step,
+        "unit": "hypergradients/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": t_step * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if wl.prec == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"config {args.config}: {wl.name}, d={wl.d}, batch {B}/{wl.X_val.shape[0]}, "
+                               f"Neumann K={K} alpha={alpha}"},
+        "roofline": {
+            "bound": "mfma",
+            "kernel": "gemm_kk_kernel (all GEMM launches of one hypergradient)",
+            "achieved": gemm_tflops,
+            "peak": PEAK_BF16_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": gemm_tflops / PEAK_BF16_TFLOPS,
+            "traffic": None,
+            "launches_per_step": gemm[0] / n_prof,
+            "avg_launch_us": gemm[1] / gemm[0] * 1e3,
+            "avg_launch_gflop": gemm[2] / gemm[0] / 1e9,
+        },
+        "hvp": {"ms": t_hvp * 1e3, "algorithmic_gflop": hvp_flops / 1e9,
+                "tflops": hvp_flops / t_hvp / 1e12, "frac_of_bf16_mfma_peak": hvp_flops / t_hvp / 1e12 / PEAK_BF16_TFLOPS},
+        "vector_kernels": {"achieved_gbs": vec_gbs, "frac_of_hbm_peak": vec_gbs / PEAK_HBM_GBS},
+        "phases": phases,
+        "fd_hypergradients_per_s": (1.0 / t_fd) if t_fd else None,
+    }
+
+    if not args.no_cpu_baseline:
+        from threadpoolctl import threadpool_info
+        from oracle import betty_oracle as orc
+        prob = orc.Problem(dims=wl.dims, act=wl.act, loss=wl.loss, hp=wl.hp, has_bias=wl.has_bias,
+                           X_tr=wl.X_tr, X_val=wl.X_val, y_tr=wl.y_tr, y_val=wl.y_val, t_tr=wl.t_tr,
+                           t_val=wl.t_val, wnet_hidden=wl.wnet_hidden)
+        reps, t_cpu = 0, 0.0
+        t0 = time.perf_counter()
+        while reps < 1 or (time.perf_counter() - t0 < 10.0 and reps < 8):
+            orc.hypergrad_neumann(prob, wl.w, wl.lam, K, alpha)
+            reps += 1
+        t_cpu = (time.perf_counter() - t0) / reps
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        result["cpu_baseline"] = {"value": 1.0 / t_cpu, "unit": "hypergradients/s", "cores": threads,
+                                  "kind": "oracle",
+                                  "sample": f"{reps} whole hypergradient(s) of the same workload (fp64 numpy oracle)"}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
