@@ -76,7 +76,8 @@ struct betty_handle_s {
   size_t scratch = 0;        // fp32 GEMM output / split-K partials
   int s_max = 16;
   size_t vec_g = 0, vec_v = 0, vec_p = 0, vec_Hv = 0, vec_wpm = 0, vec_Gm = 0;
-  size_t partials = 0, scalars = 0;
+  size_t partials = 0, scalars = 0, tickets = 0;
+  int tune_target_blocks = 512, tune_tile128_min = 128;   // see plan_chain
 
   template <typename T = void> T* at(size_t off) const { return (T*)(ws + off); }
   float* f(size_t off) const { return (float*)(ws + off); }
@@ -166,6 +167,7 @@ void plan(betty_handle h) {
   const size_t vb = h->d * 4;
   h->vec_g = pl.take(vb); h->vec_v = pl.take(vb); h->vec_p = pl.take(vb); h->vec_Hv = pl.take(vb);
   h->vec_wpm = pl.take(vb); h->vec_Gm = pl.take(vb);
+  h->tickets = pl.take((size_t)(h->max_Bp / 64) * (h->max_np / 64) * 4);
   h->partials = pl.take(1024 * 8);
   h->scalars = pl.take(256);
   h->ws_need = pl.off;
@@ -173,51 +175,71 @@ void plan(betty_handle h) {
 
 OperandSet& fd_operands(betty_handle h) { return h->sets[1].present ? h->sets[1] : h->sets[0]; }
 
-int choose_splitk(betty_handle h, Elem elem, int Mp, int Np, int Ktot_p) {
-  const int tiles = (Mp / 128) * (Np / 128);
-  const int kt = elem == ELEM_BF16 ? 32 : 16;
-  const int TT = Ktot_p / kt;
-  int S = (256 + tiles - 1) / tiles;
-  if (S > h->s_max) S = h->s_max;
-  if (S > TT) S = TT;
-  if (S < 1) S = 1;
-  return S;
+// Tile shape and K-split of an activation-shaped GEMM (M = batch): aim at about two workgroups
+// per compute unit, never fewer than two k-tiles per slice.
+struct ChainPlan { int tile, S; };
+
+ChainPlan plan_chain(betty_handle h, Elem elem, int Mp, int Np, int Ktot_p) {
+  ChainPlan cp;
+  const int tiles128 = (Mp / 128) * (Np / 128);
+  cp.tile = tiles128 >= h->tune_tile128_min ? TILE_128 : TILE_64;
+  const int tiles = cp.tile == TILE_128 ? tiles128 : 4 * tiles128;
+  const int TT = Ktot_p / gemm_ktile_elems(elem);
+  int S = (h->tune_target_blocks + tiles - 1) / tiles;
+  S = std::min(S, h->s_max);
+  S = std::min(S, std::max(1, TT / 2));
+  cp.S = std::max(S, 1);
+  return cp;
 }
 
-// fp32 GEMM into the scratch area (split-K partials), returns how to read it back
-SplitSrc gemm_to_scratch(betty_handle h, Elem elem, const void* A0, int lda0, const void* B0, int ldb0, int K0p,
-                         const void* A1, int lda1, const void* B1, int ldb1, int K1p, int M, int N,
-                         int Mp, int Np, double flops) {
-  GemmArgs g{};
+void set_pairs(GemmArgs& g, const void* A0, int lda0, const void* B0, int ldb0, int K0p, const void* A1,
+               int lda1, const void* B1, int ldb1, int K1p) {
   g.A[0] = A0; g.B[0] = B0; g.lda[0] = lda0; g.ldb[0] = ldb0; g.Kp[0] = K0p;
-  g.A[1] = A1 ? A1 : A0; g.B[1] = B1 ? B1 : B0; g.lda[1] = lda1; g.ldb[1] = ldb1; g.Kp[1] = A1 ? K1p : 0;
-  g.C = h->f(h->scratch);
-  g.ldc = Np;
-  g.M = M; g.N = N; g.Mp = Mp; g.Np = Np;
-  g.splitk = choose_splitk(h, elem, Mp, Np, g.Kp[0] + g.Kp[1]);
-  g.split_stride = (long long)Mp * Np;
-  launch_gemm(h->ctx, elem, g, flops);
-  return SplitSrc{g.C, g.ldc, g.splitk, g.split_stride};
+  g.A[1] = A1 ? A1 : A0; g.B[1] = A1 ? B1 : B0; g.lda[1] = A1 ? lda1 : lda0; g.ldb[1] = A1 ? ldb1 : ldb0;
+  g.Kp[1] = A1 ? K1p : 0;
 }
 
-void gemm_to_flat(betty_handle h, Elem elem, const void* A0, int lda0, const void* B0, int ldb0, int K0p,
-                  const void* A1, int lda1, const void* B1, int ldb1, int K1p, int M, int N, int Mp,
-                  int Np, float* C, int ldc, double flops) {
-  GemmArgs g{};
-  g.A[0] = A0; g.B[0] = B0; g.lda[0] = lda0; g.ldb[0] = ldb0; g.Kp[0] = K0p;
-  g.A[1] = A1 ? A1 : A0; g.B[1] = B1 ? B1 : B0; g.lda[1] = lda1; g.ldb[1] = ldb1; g.Kp[1] = A1 ? K1p : 0;
-  g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.Mp = Mp; g.Np = Np; g.splitk = 1; g.split_stride = 0;
-  launch_gemm(h->ctx, elem, g, flops);
+// one activation-shaped GEMM with a fused epilogue
+void chain_gemm(betty_handle h, Elem elem, const void* A0, int lda0, const void* B0, int ldb0, int K0p,
+                const void* A1, int lda1, const void* B1, int ldb1, int K1p, int M, int N, int Mp, int Np,
+                const Epilogue& e, double flops) {
+  GemmBatch b;
+  b.n = 1;
+  b.partials = h->f(h->scratch);
+  b.tickets = h->at<int>(h->tickets);
+  GemmProblem& p = b.p[0];
+  set_pairs(p.g, A0, lda0, B0, ldb0, K0p, A1, lda1, B1, ldb1, K1p);
+  p.g.M = M; p.g.N = N; p.g.Mp = Mp; p.g.Np = Np;
+  const ChainPlan cp = plan_chain(h, elem, Mp, Np, p.g.Kp[0] + p.g.Kp[1]);
+  p.g.splitk = cp.S;
+  p.e = e;
+  p.partial_base = 0;
+  p.ticket_base = 0;
+  launch_gemm_batch(h->ctx, elem, cp.tile, b, flops);
 }
 
-// operand copies of a flat parameter-shaped vector: per layer, as stored (n_in x n_out) and transposed
+Epilogue blank_epilogue(int mode, int act = 0) {
+  Epilogue e;
+  memset(&e, 0, sizeof e);
+  e.mode = mode;
+  e.act = act;
+  return e;
+}
+
+// operand copies of a flat parameter-shaped vector: per layer, as stored (n_in x n_out) and
+// transposed; all layers in one launch (eight per launch)
 void make_shadows(betty_handle h, OperandSet& os, const float* flat, float scale,
                   std::vector<size_t>* N, std::vector<size_t>* T) {
-  for (int i = 0; i < h->L; ++i) {
-    const LayerInfo& li = h->layers[i];
-    launch_convert_dual(h->ctx, os.elem, flat + li.w_off, li.n_out, scale, li.n_in, li.n_out,
-                        N ? h->at<void>((*N)[i]) : nullptr, li.n_out_p, T ? h->at<void>((*T)[i]) : nullptr,
-                        li.n_in_p);
+  for (int i0 = 0; i0 < h->L; i0 += MAX_PROBLEMS) {
+    ConvertBatch b;
+    b.n = std::min(MAX_PROBLEMS, h->L - i0);
+    for (int k = 0; k < b.n; ++k) {
+      const LayerInfo& li = h->layers[i0 + k];
+      b.j[k] = ConvertJob{flat + li.w_off, li.n_out, scale, li.n_in, li.n_out,
+                          N ? h->at<void>((*N)[i0 + k]) : nullptr, li.n_out_p,
+                          T ? h->at<void>((*T)[i0 + k]) : nullptr, li.n_in_p};
+    }
+    launch_convert_batch(h->ctx, os.elem, b);
   }
 }
 
@@ -245,24 +267,30 @@ void forward_and_loss(betty_handle h, OperandSet& os, int side, const float* w, 
   SideBuf& fb = fs.side[side];
   for (int l = 1; l <= L; ++l) {
     const LayerInfo& li = h->layers[l - 1];
-    const void* Aop = l == 1 ? h->at<void>(fb.X) : h->at<void>(fb.A[l - 1]);
-    SplitSrc src = gemm_to_scratch(h, fs.elem, Aop, li.n_in_p, h->at<void>(fs.Wt[l - 1]), li.n_in_p, li.n_in_p,
-                                   nullptr, 0, nullptr, 0, 0, B, li.n_out, Bp, li.n_out_p,
-                                   2.0 * B * li.n_in * li.n_out);
     const bool last = l == L;
-    launch_fwd_epilogue(h->ctx, fs.elem, src, h->desc.has_bias ? w + li.b_off : nullptr, h->desc.act, last,
-                        B, li.n_out, last ? h->f(sb.ZL) : nullptr, last ? nullptr : h->f(sb.dphi[l]),
-                        (!last && sb.e2[l]) ? h->f(sb.e2[l]) : nullptr, li.n_out_p,
-                        last ? nullptr : h->at<void>(fb.A[l]), li.n_out_p,
-                        (last || hybrid) ? nullptr : h->at<void>(fb.At[l]), Bp);
+    const void* Aop = l == 1 ? h->at<void>(fb.X) : h->at<void>(fb.A[l - 1]);
+    Epilogue e = blank_epilogue(last ? EPI_FWD_LAST : EPI_FWD, h->desc.act);
+    e.colvec = h->desc.has_bias ? w + li.b_off : nullptr;
+    e.ldf = li.n_out_p;
+    if (last) {
+      e.f0 = h->f(sb.ZL);
+    } else {
+      e.dphi_out = h->f(sb.dphi[l]);
+      e.d2_out = sb.e2[l] ? h->f(sb.e2[l]) : nullptr;
+      e.out = h->at<void>(fb.A[l]); e.ld = li.n_out_p;
+      e.outT = hybrid ? nullptr : h->at<void>(fb.At[l]); e.ldT = Bp;
+    }
+    chain_gemm(h, fs.elem, Aop, li.n_in_p, h->at<void>(fs.Wt[l - 1]), li.n_in_p, li.n_in_p, nullptr, 0, nullptr,
+               0, 0, B, li.n_out, Bp, li.n_out_p, e, 2.0 * B * li.n_in * li.n_out);
     if (hybrid && !last)
       launch_convert_dual(h->ctx, os.elem, h->f(fb.A[l]), li.n_out_p, 1.f, B, li.n_out, h->at<void>(sb.A[l]),
                           li.n_out_p, h->at<void>(sb.At[l]), Bp);
   }
+  (void)lower;
   const LayerInfo& lo = h->layers[L - 1];
   LossArgs a{};
   a.loss = h->desc.loss;
-  a.reweight = (lower && h->desc.hp == BETTY_HP_REWEIGHT_NET) ? 1 : 0;
+  a.reweight = (side == 0 && h->desc.hp == BETTY_HP_REWEIGHT_NET) ? 1 : 0;
   a.hidden = h->desc.wnet_hidden;
   a.Z = h->f(sb.ZL); a.ldz = lo.n_out_p;
   a.y = h->batch[side].y; a.target = h->batch[side].target; a.C = lo.n_out;
@@ -270,97 +298,147 @@ void forward_and_loss(betty_handle h, OperandSet& os, int side, const float* w, 
   a.rows = B; a.inv_batch = 1.0f / (float)B;
   a.ell = h->f(sb.ell); a.s = h->f(sb.s); a.omega = h->f(sb.omega);
   a.P = h->f(sb.P);
-  a.dZ = h->f(h->scratch); a.lddz = lo.n_out_p;
-  launch_loss_rows(h->ctx, a);
-  launch_convert_dual(h->ctx, os.elem, a.dZ, a.lddz, 1.f, B, lo.n_out, h->at<void>(sb.D[L]), lo.n_out_p,
-                      h->at<void>(sb.Dt[L]), Bp);
+  a.D = h->at<void>(sb.D[L]); a.ldD = lo.n_out_p;
+  a.Dt = h->at<void>(sb.Dt[L]); a.ldDt = Bp;
+  launch_loss_rows(h->ctx, os.elem, a);
 }
 
-// delta_l for every layer; parameter gradient into grad_or_null (data term only)
-void backward(betty_handle h, OperandSet& os, int side, float* grad_or_null) {
+// delta_l for every layer below the output (and (delta W^T) phi'' on the lower side)
+void backward_chain(betty_handle h, OperandSet& os, int side) {
   SideBuf& sb = os.side[side];
   const int L = h->L, B = sb.B, Bp = sb.Bp;
-  for (int l = L; l >= 1; --l) {
+  for (int l = L; l >= 2; --l) {
     const LayerInfo& li = h->layers[l - 1];
-    if (grad_or_null) {
-      const void* AT = l == 1 ? h->at<void>(sb.XT) : h->at<void>(sb.At[l - 1]);
-      gemm_to_flat(h, os.elem, AT, Bp, h->at<void>(sb.Dt[l]), Bp, Bp, nullptr, 0, nullptr, 0, 0,
-                   li.n_in, li.n_out, li.n_in_p, li.n_out_p, grad_or_null + li.w_off, li.n_out,
-                   2.0 * B * li.n_in * li.n_out);
-      if (h->desc.has_bias)
-        launch_row_sums(h->ctx, os.elem, h->at<void>(sb.Dt[l]), Bp, li.n_out, B, grad_or_null + li.b_off);
-    }
-    if (l > 1) {
-      SplitSrc src = gemm_to_scratch(h, os.elem, h->at<void>(sb.D[l]), li.n_out_p, h->at<void>(os.Wn[l - 1]),
-                                     li.n_out_p, li.n_out_p, nullptr, 0, nullptr, 0, 0, B, li.n_in, Bp,
-                                     li.n_in_p, 2.0 * B * li.n_in * li.n_out);
-      launch_bwd_epilogue(h->ctx, os.elem, src, h->f(sb.dphi[l - 1]),
-                          sb.e2[l - 1] ? h->f(sb.e2[l - 1]) : nullptr, li.n_in_p, B, li.n_in,
-                          h->at<void>(sb.D[l - 1]), li.n_in_p, h->at<void>(sb.Dt[l - 1]), Bp);
-    }
+    Epilogue e = blank_epilogue(EPI_BWD);
+    e.dphi = h->f(sb.dphi[l - 1]);
+    e.e_io = sb.e2[l - 1] ? h->f(sb.e2[l - 1]) : nullptr;
+    e.ldf = li.n_in_p;
+    e.out = h->at<void>(sb.D[l - 1]); e.ld = li.n_in_p;
+    e.outT = h->at<void>(sb.Dt[l - 1]); e.ldT = Bp;
+    chain_gemm(h, os.elem, h->at<void>(sb.D[l]), li.n_out_p, h->at<void>(os.Wn[l - 1]), li.n_out_p, li.n_out_p,
+               nullptr, 0, nullptr, 0, 0, B, li.n_in, Bp, li.n_in_p, e, 2.0 * B * li.n_in * li.n_out);
   }
 }
 
-// R-forward along the direction whose operand copies are in os.Vn / os.Vt and whose fp32 flat
-// form is `vflat` (for the bias directions).  Leaves Rz_l (fp32) and Ra_l.
-void r_forward(betty_handle h, OperandSet& os, const float* vflat, float vscale) {
+// What the grouped weight-gradient launch does with its result.
+struct WgradSink {
+  int mode;                 // EPI_WGRAD / EPI_WGRAD_INIT / EPI_WGRAD_NEUMANN
+  float* C;                 // flat output (EPI_WGRAD)
+  const float* lam;         // non-null adds the L2-decay term 2 e^lam x
+  const float* x;
+  float* v; float* p; float alpha;
+  bool copies;              // also write the operand copies of the new v
+};
+
+// All layers' parameter-shaped products in one launch: plain gradient a^T delta (rop = false) or
+// the R-op form Ra^T delta + a^T Rdelta (rop = true), bias rows included.
+void wgrad_batch(betty_handle h, OperandSet& os, int side, bool rop, const WgradSink& k) {
+  SideBuf& sb = os.side[side];
+  const int L = h->L, B = sb.B, Bp = sb.Bp;
+  for (int l0 = 1; l0 <= L; l0 += MAX_PROBLEMS) {
+    GemmBatch b;
+    b.partials = h->f(h->scratch);
+    b.tickets = h->at<int>(h->tickets);
+    b.n = std::min(MAX_PROBLEMS, L - l0 + 1);
+    double flops = 0;
+    for (int i = 0; i < b.n; ++i) {
+      const int l = l0 + i;
+      const LayerInfo& li = h->layers[l - 1];
+      GemmProblem& p = b.p[i];
+      const void* aT = l == 1 ? h->at<void>(sb.XT) : h->at<void>(sb.At[l - 1]);
+      if (!rop) {
+        set_pairs(p.g, aT, Bp, h->at<void>(sb.Dt[l]), Bp, Bp, nullptr, 0, nullptr, 0, 0);
+        flops += 2.0 * B * li.n_in * li.n_out;
+      } else if (l == 1) {
+        set_pairs(p.g, aT, Bp, h->at<void>(os.RDt[l]), Bp, Bp, nullptr, 0, nullptr, 0, 0);
+        flops += 2.0 * B * li.n_in * li.n_out;
+      } else {
+        set_pairs(p.g, h->at<void>(os.RAt[l - 1]), Bp, h->at<void>(sb.Dt[l]), Bp, Bp, aT, Bp,
+                  h->at<void>(os.RDt[l]), Bp, Bp);
+        flops += 4.0 * B * li.n_in * li.n_out;
+      }
+      p.g.M = li.n_in; p.g.N = li.n_out; p.g.Mp = li.n_in_p; p.g.Np = li.n_out_p; p.g.splitk = 1;
+      p.partial_base = 0; p.ticket_base = 0;
+      Epilogue e = blank_epilogue(k.mode);
+      e.ldc = li.n_out;
+      e.C = k.C ? k.C + li.w_off : nullptr;
+      e.lam = k.lam ? k.lam + li.w_off : nullptr;
+      e.x = k.x ? k.x + li.w_off : nullptr;
+      e.v = k.v ? k.v + li.w_off : nullptr;
+      e.p = k.p ? k.p + li.w_off : nullptr;
+      e.alpha = k.alpha;
+      if (k.copies) {
+        e.out = h->at<void>(os.Vn[l - 1]); e.ld = li.n_out_p;
+        e.outT = h->at<void>(os.Vt[l - 1]); e.ldT = li.n_in_p;
+      }
+      p.e = e;
+      if (h->desc.has_bias) {
+        BiasJob& j = b.bias[b.n_bias++];
+        j.Mt = rop ? h->at<void>(os.RDt[l]) : h->at<void>(sb.Dt[l]);
+        j.ld = Bp; j.rows = li.n_out; j.k = B; j.mode = k.mode;
+        j.C = k.C ? k.C + li.b_off : nullptr;
+        j.lam = k.lam ? k.lam + li.b_off : nullptr;
+        j.x = k.x ? k.x + li.b_off : nullptr;
+        j.v = k.v ? k.v + li.b_off : nullptr;
+        j.p = k.p ? k.p + li.b_off : nullptr;
+        j.alpha = k.alpha;
+      }
+    }
+    launch_gemm_batch(h->ctx, os.elem, TILE_128, b, flops);
+  }
+}
+
+// R-forward along the direction whose operand copies are in os.Vt and whose fp32 flat form is
+// `vflat` (for the bias directions).  Leaves Rz_l (fp32) and Ra_l.
+void r_forward(betty_handle h, OperandSet& os, const float* vflat) {
   SideBuf& sb = os.side[0];
   const int L = h->L, B = sb.B, Bp = sb.Bp;
-  (void)vscale;
   for (int l = 1; l <= L; ++l) {
     const LayerInfo& li = h->layers[l - 1];
-    const void* a_prev = l == 1 ? h->at<void>(sb.X) : h->at<void>(sb.A[l - 1]);
-    SplitSrc src;
-    if (l == 1) {
-      src = gemm_to_scratch(h, os.elem, a_prev, li.n_in_p, h->at<void>(os.Vt[0]), li.n_in_p, li.n_in_p,
-                            nullptr, 0, nullptr, 0, 0, B, li.n_out, Bp, li.n_out_p,
-                            2.0 * B * li.n_in * li.n_out);
-    } else {
-      src = gemm_to_scratch(h, os.elem, h->at<void>(os.RA[l - 1]), li.n_in_p, h->at<void>(os.Wt[l - 1]),
-                            li.n_in_p, li.n_in_p, a_prev, li.n_in_p, h->at<void>(os.Vt[l - 1]), li.n_in_p,
-                            li.n_in_p, B, li.n_out, Bp, li.n_out_p, 4.0 * B * li.n_in * li.n_out);
-    }
     const bool last = l == L;
-    launch_rfwd_epilogue(h->ctx, os.elem, src, h->desc.has_bias ? vflat + li.b_off : nullptr, last,
-                         last ? nullptr : h->f(sb.dphi[l]), h->f(os.Rz[l]), li.n_out_p, B, li.n_out,
-                         last ? nullptr : h->at<void>(os.RA[l]), li.n_out_p,
-                         last ? nullptr : h->at<void>(os.RAt[l]), Bp);
+    const void* a_prev = l == 1 ? h->at<void>(sb.X) : h->at<void>(sb.A[l - 1]);
+    Epilogue e = blank_epilogue(last ? EPI_RFWD_LAST : EPI_RFWD);
+    e.colvec = h->desc.has_bias ? vflat + li.b_off : nullptr;
+    e.f0 = h->f(os.Rz[l]);
+    e.ldf = li.n_out_p;
+    if (!last) {
+      e.dphi = h->f(sb.dphi[l]);
+      e.out = h->at<void>(os.RA[l]); e.ld = li.n_out_p;
+      e.outT = h->at<void>(os.RAt[l]); e.ldT = Bp;
+    }
+    if (l == 1)
+      chain_gemm(h, os.elem, a_prev, li.n_in_p, h->at<void>(os.Vt[0]), li.n_in_p, li.n_in_p, nullptr, 0, nullptr,
+                 0, 0, B, li.n_out, Bp, li.n_out_p, e, 2.0 * B * li.n_in * li.n_out);
+    else
+      chain_gemm(h, os.elem, h->at<void>(os.RA[l - 1]), li.n_in_p, h->at<void>(os.Wt[l - 1]), li.n_in_p,
+                 li.n_in_p, a_prev, li.n_in_p, h->at<void>(os.Vt[l - 1]), li.n_in_p, li.n_in_p, B, li.n_out, Bp,
+                 li.n_out_p, e, 4.0 * B * li.n_in * li.n_out);
   }
 }
 
-// Hv (data term) with the forward/backward cache of the train batch in place
-void hvp_cached(betty_handle h, OperandSet& os, const float* vflat, float* Hv) {
+// One Hessian-vector product with the forward/backward cache of the train batch in place; the
+// parameter-shaped result goes where `sink` says (plain store, or fused into the recurrence).
+void hvp_cached(betty_handle h, OperandSet& os, const float* vflat, const WgradSink& sink) {
   SideBuf& sb = os.side[0];
   const int L = h->L, B = sb.B, Bp = sb.Bp;
-  r_forward(h, os, vflat, 1.f);
+  r_forward(h, os, vflat);
   const LayerInfo& lo = h->layers[L - 1];
-  launch_loss_hessian_rows(h->ctx, h->desc.loss, h->f(sb.P), h->f(os.Rz[L]), lo.n_out_p, h->f(sb.s), B,
-                           lo.n_out, h->f(h->scratch), lo.n_out_p);
-  launch_convert_dual(h->ctx, os.elem, h->f(h->scratch), lo.n_out_p, 1.f, B, lo.n_out,
-                      h->at<void>(os.RD[L]), lo.n_out_p, h->at<void>(os.RDt[L]), Bp);
-  for (int l = L; l >= 1; --l) {
+  launch_loss_hessian_rows(h->ctx, os.elem, h->desc.loss, h->f(sb.P), h->f(os.Rz[L]), lo.n_out_p, h->f(sb.s), B,
+                           lo.n_out, h->at<void>(os.RD[L]), lo.n_out_p, h->at<void>(os.RDt[L]), Bp);
+  for (int l = L; l >= 2; --l) {
     const LayerInfo& li = h->layers[l - 1];
-    const void* aT = l == 1 ? h->at<void>(sb.XT) : h->at<void>(sb.At[l - 1]);
-    if (l == 1) {
-      gemm_to_flat(h, os.elem, aT, Bp, h->at<void>(os.RDt[l]), Bp, Bp, nullptr, 0, nullptr, 0, 0, li.n_in,
-                   li.n_out, li.n_in_p, li.n_out_p, Hv + li.w_off, li.n_out, 2.0 * B * li.n_in * li.n_out);
-    } else {
-      gemm_to_flat(h, os.elem, h->at<void>(os.RAt[l - 1]), Bp, h->at<void>(sb.Dt[l]), Bp, Bp, aT, Bp,
-                   h->at<void>(os.RDt[l]), Bp, Bp, li.n_in, li.n_out, li.n_in_p, li.n_out_p,
-                   Hv + li.w_off, li.n_out, 4.0 * B * li.n_in * li.n_out);
-    }
-    if (h->desc.has_bias)
-      launch_row_sums(h->ctx, os.elem, h->at<void>(os.RDt[l]), Bp, li.n_out, B, Hv + li.b_off);
-    if (l > 1) {
-      SplitSrc src = gemm_to_scratch(h, os.elem, h->at<void>(os.RD[l]), li.n_out_p, h->at<void>(os.Wn[l - 1]),
-                                     li.n_out_p, li.n_out_p, h->at<void>(sb.D[l]), li.n_out_p,
-                                     h->at<void>(os.Vn[l - 1]), li.n_out_p, li.n_out_p, B, li.n_in, Bp,
-                                     li.n_in_p, 4.0 * B * li.n_in * li.n_out);
-      launch_rbwd_epilogue(h->ctx, os.elem, src, h->f(sb.dphi[l - 1]),
-                           sb.e2[l - 1] ? h->f(sb.e2[l - 1]) : nullptr, h->f(os.Rz[l - 1]), li.n_in_p, B,
-                           li.n_in, h->at<void>(os.RD[l - 1]), li.n_in_p, h->at<void>(os.RDt[l - 1]), Bp);
-    }
+    Epilogue e = blank_epilogue(EPI_RBWD);
+    e.dphi = h->f(sb.dphi[l - 1]);
+    e.e = sb.e2[l - 1] ? h->f(sb.e2[l - 1]) : nullptr;
+    e.Rz = h->f(os.Rz[l - 1]);
+    e.ldf = li.n_in_p;
+    e.out = h->at<void>(os.RD[l - 1]); e.ld = li.n_in_p;
+    e.outT = h->at<void>(os.RDt[l - 1]); e.ldT = Bp;
+    chain_gemm(h, os.elem, h->at<void>(os.RD[l]), li.n_out_p, h->at<void>(os.Wn[l - 1]), li.n_out_p, li.n_out_p,
+               h->at<void>(sb.D[l]), li.n_out_p, h->at<void>(os.Vn[l - 1]), li.n_out_p, li.n_out_p, B, li.n_in, Bp,
+               li.n_in_p, e, 4.0 * B * li.n_in * li.n_out);
   }
+  wgrad_batch(h, os, 0, true, sink);
 }
 
 // full first-order gradient of the lower cost at w (operand copies of w already made)
@@ -368,8 +446,9 @@ void lower_grad_seq(betty_handle h, OperandSet& os, const float* w, const float*
                     float* loss_or_null) {
   const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
   forward_and_loss(h, os, 0, w, l2 ? nullptr : lam);
-  backward(h, os, 0, grad);
-  if (l2) launch_add_l2_term(h->ctx, grad, lam, w, h->d);
+  backward_chain(h, os, 0);
+  WgradSink k{EPI_WGRAD, grad, l2 ? lam : nullptr, l2 ? w : nullptr, nullptr, nullptr, 0.f, false};
+  wgrad_batch(h, os, 0, false, k);
   if (loss_or_null) {
     float* add = nullptr;
     if (l2) {
@@ -380,9 +459,11 @@ void lower_grad_seq(betty_handle h, OperandSet& os, const float* w, const float*
   }
 }
 
-void upper_grad_seq(betty_handle h, OperandSet& os, const float* w, float* grad, float* loss_or_null) {
+// gradient of the upper cost on the validation batch; the result goes where `sink` says
+void upper_grad_seq(betty_handle h, OperandSet& os, const float* w, const WgradSink& sink, float* loss_or_null) {
   forward_and_loss(h, os, 1, w, nullptr);
-  backward(h, os, 1, grad);
+  backward_chain(h, os, 1);
+  wgrad_batch(h, os, 1, false, sink);
   if (loss_or_null)
     launch_weighted_loss_sum(h->ctx, h->f(os.side[1].s), h->f(os.side[1].ell), os.side[1].B, nullptr, loss_or_null);
 }
@@ -390,7 +471,7 @@ void upper_grad_seq(betty_handle h, OperandSet& os, const float* w, float* grad,
 // forward/backward cache of the train batch for the R-op passes (no parameter gradient)
 void prepare_lower(betty_handle h, OperandSet& os, const float* w, const float* lam) {
   forward_and_loss(h, os, 0, w, h->desc.hp == BETTY_HP_L2_DECAY ? nullptr : lam);
-  backward(h, os, 0, nullptr);
+  backward_chain(h, os, 0);
 }
 
 // out = -(1/B) sum_i c_i dR/dtheta with c_i = <grad_w l_i, scale * qflat>
@@ -400,15 +481,15 @@ void mixed_reweight_seq(betty_handle h, OperandSet& os, const float* lam, const 
   const int L = h->L;
   const LayerInfo& lo = h->layers[L - 1];
   // the direction is scale * qflat: scale once into a flat fp32 copy (its bias slices feed the
-  // R-forward epilogues), then make the operand copies from that
+  // R-forward epilogues), then make the transposed operand copies the R-forward needs
   const float* qs = qflat;
   if (scale != 1.f) {
     float* tmp = h->f(h->vec_wpm);
     launch_scale_copy(h->ctx, qflat, scale, tmp, h->d);
     qs = tmp;
   }
-  make_shadows(h, os, qs, 1.f, &os.Vn, &os.Vt);
-  r_forward(h, os, qs, 1.f);
+  make_shadows(h, os, qs, 1.f, nullptr, &os.Vt);
+  r_forward(h, os, qs);
   launch_loss_directional_rows(h->ctx, h->desc.loss, h->f(sb.P), h->f(sb.ZL), h->batch[0].y,
                                h->batch[0].target, h->f(os.Rz[L]), lo.n_out_p, sb.B, lo.n_out, h->f(os.cvec));
   launch_wnet_theta_vjp(h->ctx, h->f(sb.ell), h->f(sb.omega), h->f(os.cvec), lam, h->desc.wnet_hidden, sb.B,
@@ -558,7 +639,8 @@ betty_status betty_upper_grad(betty_handle h, const float* w, float* grad_w, flo
   if (overlaps(grad_w, h->d * 4, w, h->d * 4)) return fail(h, BETTY_EINVAL, "grad_w overlaps w");
   OperandSet& os = h->sets[0];
   make_weight_operands(h, os, w);
-  upper_grad_seq(h, os, w, grad_w, loss_or_null);
+  WgradSink k{EPI_WGRAD, grad_w, nullptr, nullptr, nullptr, nullptr, 0.f, false};
+  upper_grad_seq(h, os, w, k, loss_or_null);
   return finish(h);
 }
 
@@ -573,8 +655,9 @@ betty_status betty_hvp(betty_handle h, const float* w, const float* lambda, cons
   make_weight_operands(h, os, w);
   prepare_lower(h, os, w, lambda);
   make_shadows(h, os, v, 1.f, &os.Vn, &os.Vt);
-  hvp_cached(h, os, v, Hv);
-  if (h->desc.hp == BETTY_HP_L2_DECAY) launch_add_l2_term(h->ctx, Hv, lambda, v, h->d);
+  const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
+  WgradSink k{EPI_WGRAD, Hv, l2 ? lambda : nullptr, l2 ? v : nullptr, nullptr, nullptr, 0.f, false};
+  hvp_cached(h, os, v, k);
   return finish(h);
 }
 
@@ -612,16 +695,16 @@ betty_status betty_hypergrad_neumann(betty_handle h, const float* w, const float
   CHECK(check_hyper_args(h, w, lambda, K, alpha, dlambda));
   OperandSet& os = h->sets[0];
   const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
-  float* g = h->f(h->vec_g); float* v = h->f(h->vec_v); float* p = h->f(h->vec_p); float* Hv = h->f(h->vec_Hv);
+  float* v = h->f(h->vec_v); float* p = h->f(h->vec_p);
   make_weight_operands(h, os, w);
-  upper_grad_seq(h, os, w, g, nullptr);
+  // g = grad_w L_U lands directly in v and p, with the operand copies of v for the first product
+  WgradSink init{EPI_WGRAD_INIT, nullptr, nullptr, nullptr, v, p, 0.f, K > 0};
+  upper_grad_seq(h, os, w, init, nullptr);
   if (K > 0 || !l2) prepare_lower(h, os, w, lambda);
-  launch_copy2(h->ctx, g, v, p, h->d);
   for (int k = 0; k < K; ++k) {
-    make_shadows(h, os, v, 1.f, &os.Vn, &os.Vt);
-    hvp_cached(h, os, v, Hv);
-    if (l2) launch_add_l2_term(h->ctx, Hv, lambda, v, h->d);
-    launch_neumann_update(h->ctx, v, p, Hv, alpha, h->d);
+    // v <- v - alpha (H v), p <- p + v fused into the weight-gradient epilogues of the product
+    WgradSink step{EPI_WGRAD_NEUMANN, nullptr, l2 ? lambda : nullptr, nullptr, v, p, alpha, k + 1 < K};
+    hvp_cached(h, os, v, step);
   }
   if (l2) launch_mixed_l2(h->ctx, lambda, w, p, alpha, dlambda, h->d);
   else mixed_reweight_seq(h, os, lambda, p, alpha, dlambda);
@@ -635,12 +718,12 @@ betty_status betty_hypergrad_fd(betty_handle h, const float* w, const float* lam
   if (h->desc.hp != BETTY_HP_L2_DECAY)
     return fail(h, BETTY_EUNSUPPORTED, "finite-difference variant is implemented for L2-decay hyperparameters only");
   OperandSet& os = fd_operands(h);
-  float* g = h->f(h->vec_g); float* v = h->f(h->vec_v); float* p = h->f(h->vec_p); float* Gp = h->f(h->vec_Hv);
+  float* v = h->f(h->vec_v); float* p = h->f(h->vec_p); float* Gp = h->f(h->vec_Hv);
   float* Gm = h->f(h->vec_Gm); float* wpm = h->f(h->vec_wpm);
   float* nrm2 = h->f(h->scalars); float* eps = h->f(h->scalars) + 1;
   make_weight_operands(h, os, w);
-  upper_grad_seq(h, os, w, g, nullptr);
-  launch_copy2(h->ctx, g, v, p, h->d);
+  WgradSink init{EPI_WGRAD_INIT, nullptr, nullptr, nullptr, v, p, 0.f, false};
+  upper_grad_seq(h, os, w, init, nullptr);
   for (int k = 0; k < K; ++k) {
     launch_sumsq(h->ctx, v, h->d, h->at<double>(h->partials), nrm2);
     launch_fd_eps(h->ctx, nrm2, eps_scale, 1.f, eps);

@@ -21,20 +21,68 @@ inline int padup(int n) { return (n + PAD - 1) / PAD * PAD; }
 enum Elem { ELEM_F32 = 0, ELEM_BF16 = 1 };
 inline size_t elem_size(Elem e) { return e == ELEM_F32 ? 4 : 2; }
 
-// C (fp32) = sum over up to two operand pairs of A_p (M x K_p) * B_p^T (B_p is N x K_p).
+// Accumulators = sum over up to two operand pairs of A_p (M x K_p) * B_p^T (B_p is N x K_p).
 // Both operands are "K-major": element (row, k) at base[row * ld + k].
 struct GemmArgs {
   const void* A[2];
   const void* B[2];
   int lda[2], ldb[2];        // leading dimensions in elements
   int Kp[2];                 // padded reduction extents in elements; 0 = pair absent
-  float* C;
-  long long ldc;
-  int M, N;                  // valid output extent (stores are bounds-checked against it)
-  int Mp, Np;                // padded extents (define the grid)
-  int splitk;                // number of K slices; slice s writes C + s * split_stride
-  long long split_stride;
+  int M, N;                  // valid output extent (epilogue stores are bounds-checked against it)
+  int Mp, Np;                // padded extents (define the tile grid)
+  int splitk;                // number of K slices per tile
 };
+
+// What happens to a finished accumulator tile.
+enum EpiMode {
+  EPI_STORE = 0,         // C[row][col] = acc
+  EPI_FWD,               // z = acc + bias; out = phi(z); dphi_out = phi'(z); d2_out = phi''(z)
+  EPI_FWD_LAST,          // f0 = acc + bias                       (logits)
+  EPI_BWD,               // out = acc * dphi; e_io = acc * e_io   (delta of the layer below)
+  EPI_RFWD,              // f0 = rz = acc + cbias; out = dphi * rz
+  EPI_RFWD_LAST,         // f0 = acc + cbias
+  EPI_RBWD,              // out = acc * dphi + e * Rz
+  EPI_WGRAD,             // C = acc (+ 2 exp(lam) x)                       flat parameter layout
+  EPI_WGRAD_INIT,        // v = p = acc; out = operand copies of v
+  EPI_WGRAD_NEUMANN      // Hv = acc (+ 2 exp(lam) v); v -= alpha Hv; p += v; out = copies of v
+};
+
+struct Epilogue {
+  int mode, act;
+  const float* colvec;                   // per-column addend (bias or bias direction), may be null
+  float* f0;                             // fp32 [row * ldf + col]
+  float* dphi_out; float* d2_out;
+  const float* dphi; float* e_io; const float* e; const float* Rz;
+  long long ldf;
+  void* out; int ld;                     // operand-typed, row-major [row][col]
+  void* outT; int ldT;                   // operand-typed, transposed [col][row]
+  float* C; long long ldc;               // fp32 row-major (flat parameter slice for the WGRAD modes)
+  const float* lam; const float* x;      // same indexing as C
+  float* v; float* p; float alpha;
+};
+
+struct GemmProblem { GemmArgs g; Epilogue e; long long partial_base; int ticket_base; };
+
+// out[row] from sum_k Mt[row][k]: bias-shaped slices of the WGRAD modes
+struct BiasJob {
+  const void* Mt; int ld, rows, k, mode;
+  float* C; const float* lam; const float* x; float* v; float* p; float alpha;
+};
+
+constexpr int MAX_PROBLEMS = 8;
+constexpr int GEMM_NCH = 8;              // 16-byte chunks per row of a k-tile
+enum { TILE_128 = 0, TILE_64 = 1 };
+
+struct GemmBatch {
+  int n = 0, n_bias = 0, gemm_blocks = 0;
+  int block_begin[MAX_PROBLEMS + 1];
+  int bias_begin[MAX_PROBLEMS + 1];
+  float* partials = nullptr;             // split-K slices, (tile, slice, register, thread) order
+  int* tickets = nullptr;                // one arrival counter per tile, zero between launches
+  GemmProblem p[MAX_PROBLEMS];
+  BiasJob bias[MAX_PROBLEMS];
+};
+static_assert(sizeof(GemmBatch) <= 3584, "GemmBatch is passed by value as a kernel argument (4 KiB limit)");
 
 // Launch context: stream + optional per-launch event timing.
 struct ProfRec { int kind; double flops, bytes; hipEvent_t e0, e1; float ms; };
@@ -54,29 +102,21 @@ struct Launch {   // RAII bracket around one kernel launch
 };
 
 // ---- gemm.hip
-void launch_gemm(Ctx& ctx, Elem elem, const GemmArgs& g, double algorithmic_flops);
+int gemm_ktile_elems(Elem elem);
+void launch_gemm_batch(Ctx& ctx, Elem elem, int tile, GemmBatch& batch, double algorithmic_flops);
 
-// ---- kernels.hip : fused elementwise stages ------------------------------------------------
-// "dual" outputs: out is [rows_p][ld] row-major, outT is [cols_p][ldT]; either may be null.
-
-struct SplitSrc { const float* part; long long ld; int S; long long stride; };
-
-// a = phi(sum_s part + bias); writes dphi (and d2phi for GELU) in fp32; last layer writes z only
-void launch_fwd_epilogue(Ctx&, Elem, SplitSrc src, const float* bias_or_null, int act, bool last,
-                         int rows, int cols, float* z_out_or_null, float* dphi, float* d2phi_or_null,
-                         long long ldf, void* out, int ld, void* outT, int ldT);
-// delta = t * dphi,  e = t * d2phi (in place over d2phi) with t = sum_s part
-void launch_bwd_epilogue(Ctx&, Elem, SplitSrc src, const float* dphi, float* e_inout_or_null,
-                         long long ldf, int rows, int cols, void* out, int ld, void* outT, int ldT);
-// Rz = sum_s part + cbias; Ra = dphi * Rz (hidden layers)
-void launch_rfwd_epilogue(Ctx&, Elem, SplitSrc src, const float* cbias_or_null, bool last,
-                          const float* dphi_or_null, float* Rz, long long ldf, int rows, int cols,
-                          void* out, int ld, void* outT, int ldT);
-// Rdelta = t * dphi + e * Rz
-void launch_rbwd_epilogue(Ctx&, Elem, SplitSrc src, const float* dphi, const float* e_or_null,
-                          const float* Rz, long long ldf, int rows, int cols, void* out, int ld,
-                          void* outT, int ldT);
-// out/outT = convert(scale * src[r * lds + c])
+// ---- kernels.hip : operand conversion -----------------------------------------------------
+// out (row-major [rows_p][ld]) and outT ([cols_p][ldT]) = convert(scale * src[r * lds + c]); either may be null
+struct ConvertJob {
+  const float* src; long long lds; float scale; int rows, cols;
+  void* out; int ld; void* outT; int ldT;
+};
+struct ConvertBatch {
+  int n = 0;
+  int block_begin[MAX_PROBLEMS + 1];
+  ConvertJob j[MAX_PROBLEMS];
+};
+void launch_convert_batch(Ctx&, Elem, ConvertBatch&);
 void launch_convert_dual(Ctx&, Elem, const float* src, long long lds, float scale, int rows,
                          int cols, void* out, int ld, void* outT, int ldT);
 
@@ -89,12 +129,12 @@ struct LossArgs {
   int rows; float inv_batch;
   float* ell; float* s; float* omega;   // per-sample outputs
   float* P;                             // softmax probabilities [rows][ldz] (CE)
-  float* dZ; long long lddz;            // s_i * dl_i/dz  (fp32 scratch)
+  void* D; int ldD; void* Dt; int ldDt;  // s_i * dl_i/dz as GEMM operands, both orientations
 };
-void launch_loss_rows(Ctx&, const LossArgs&);
+void launch_loss_rows(Ctx&, Elem, const LossArgs&);
 // Rdelta_L (fp32) = s_i * (d^2 l_i/dz^2) Rz_i
-void launch_loss_hessian_rows(Ctx&, int loss, const float* P, const float* Rz, long long ld,
-                              const float* s, int rows, int C, float* out, long long ldo);
+void launch_loss_hessian_rows(Ctx&, Elem, int loss, const float* P, const float* Rz, long long ld,
+                              const float* s, int rows, int C, void* D, int ldD, void* Dt, int ldDt);
 // c_i = < dl_i/dz, Rz_i >
 void launch_loss_directional_rows(Ctx&, int loss, const float* P, const float* Z, const int32_t* y,
                                   const float* target, const float* Rz, long long ld, int rows,
@@ -102,15 +142,10 @@ void launch_loss_directional_rows(Ctx&, int loss, const float* P, const float* Z
 // out = -(1/B) sum_i c_i dR(l_i; theta)/dtheta
 void launch_wnet_theta_vjp(Ctx&, const float* ell, const float* omega, const float* c,
                            const float* theta, int hidden, int rows, float inv_batch, float* out);
-// bias-shaped sums: out[r] = sum_k M[r][k]   (rows of a K-major operand matrix)
-void launch_row_sums(Ctx&, Elem, const void* Mtx, int ld, int rows, int k, float* out);
 
 // ---- kernels.hip : flat parameter-shaped vectors ------------------------------------------
 void launch_fill_zero(Ctx&, void* p, size_t bytes);
-void launch_copy2(Ctx&, const float* src, float* a, float* b, size_t n);
 void launch_scale_copy(Ctx&, const float* src, float scale, float* dst, size_t n);
-void launch_add_l2_term(Ctx&, float* out, const float* lam, const float* x, size_t n);   // out += 2 e^lam x
-void launch_neumann_update(Ctx&, float* v, float* p, const float* Hv, float alpha, size_t n);
 void launch_mixed_l2(Ctx&, const float* lam, const float* w, const float* p, float alpha, float* out, size_t n);
 void launch_sumsq(Ctx&, const float* x, size_t n, double* partials, float* out_scalar);
 void launch_l2_cost(Ctx&, const float* lam, const float* w, size_t n, double* partials, float* out_scalar);

@@ -41,44 +41,30 @@ template <> __device__ __forceinline__ float from_float<float>(float x) { return
 template <> __device__ __forceinline__ __bf16 from_float<__bf16>(float x) { return (__bf16)x; }  // RNE
 template <typename T> __device__ __forceinline__ float to_float(T x) { return (float)x; }
 
-// phi, phi', phi'' ; GELU is the exact erf form, ReLU has derivative 0 at 0
-__device__ __forceinline__ void act_eval(int act, float z, float& a, float& d1, float& d2) {
-  if (act == BETTY_ACT_RELU) {
-    const bool pos = z > 0.f;
-    a = pos ? z : 0.f; d1 = pos ? 1.f : 0.f; d2 = 0.f;
-  } else if (act == BETTY_ACT_GELU_ERF) {
-    const float Phi = 0.5f * (1.f + erff(z * 0.70710678118654752f));
-    const float pdf = 0.39894228040143268f * expf(-0.5f * z * z);
-    a = z * Phi; d1 = Phi + z * pdf; d2 = pdf * (2.f - z * z);
-  } else {
-    a = z; d1 = 1.f; d2 = 0.f;
-  }
-}
-
-__device__ __forceinline__ float split_sum(const SplitSrc& s, int r, int c) {
-  const float* p = s.part + (long long)r * s.ld + c;
-  float t = p[0];
-  for (int k = 1; k < s.S; ++k) t += p[(long long)k * s.stride];
-  return t;
-}
-
 // ------------------------------------------------------------------------------------------
-// 64x64 tile kernel: value f(r, c) -> row-major `out` and transposed `outT`
+// operand conversion: fp32 source -> operand type, row-major and transposed, through a 64x64
+// LDS tile; up to MAX_PROBLEMS matrices per launch
 // ------------------------------------------------------------------------------------------
 
-template <typename T, typename F>
-__global__ __launch_bounds__(256) void tile_dual_kernel(F f, int rows, int cols, T* out, int ld,
-                                                        T* outT, int ldT) {
+template <typename T>
+__global__ __launch_bounds__(256) void convert_batch_kernel(ConvertBatch b) {
   __shared__ float tile[64][65];
-  const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+  int bid = blockIdx.x, ji = 0;
+  while (ji + 1 < b.n && bid >= b.block_begin[ji + 1]) ++ji;
+  const ConvertJob& j = b.j[ji];
+  bid -= b.block_begin[ji];
+  const int tiles_x = (j.cols + 63) / 64;
+  const int c0 = (bid % tiles_x) * 64, r0 = (bid / tiles_x) * 64;
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  T* out = (T*)j.out;
+  T* outT = (T*)j.outT;
 #pragma unroll 4
   for (int i = 0; i < 16; ++i) {
     const int r = r0 + ty + 4 * i, c = c0 + tx;
     float val = 0.f;
-    if (r < rows && c < cols) {
-      val = f(r, c);
-      if (out) out[(long long)r * ld + c] = from_float<T>(val);
+    if (r < j.rows && c < j.cols) {
+      val = j.scale * j.src[(long long)r * j.lds + c];
+      if (out) out[(long long)r * j.ld + c] = from_float<T>(val);
     }
     tile[ty + 4 * i][tx] = val;
   }
@@ -87,115 +73,38 @@ __global__ __launch_bounds__(256) void tile_dual_kernel(F f, int rows, int cols,
 #pragma unroll 4
   for (int i = 0; i < 16; ++i) {
     const int c = c0 + ty + 4 * i, r = r0 + tx;
-    if (r < rows && c < cols) outT[(long long)c * ldT + r] = from_float<T>(tile[tx][ty + 4 * i]);
+    if (r < j.rows && c < j.cols) outT[(long long)c * j.ldT + r] = from_float<T>(tile[tx][ty + 4 * i]);
   }
 }
 
-template <typename F>
-static void launch_tile_dual(Ctx& ctx, Elem elem, int kind, double bytes, F f, int rows, int cols,
-                             void* out, int ld, void* outT, int ldT) {
-  if (rows <= 0 || cols <= 0) return;
-  dim3 grid((cols + 63) / 64, (rows + 63) / 64);
-  Launch l(ctx, kind, 0, bytes);
-  if (elem == ELEM_BF16)
-    tile_dual_kernel<__bf16, F><<<grid, 256, 0, ctx.stream>>>(f, rows, cols, (__bf16*)out, ld, (__bf16*)outT, ldT);
-  else
-    tile_dual_kernel<float, F><<<grid, 256, 0, ctx.stream>>>(f, rows, cols, (float*)out, ld, (float*)outT, ldT);
-}
-
-struct FwdEpi {
-  SplitSrc src; const float* bias; int act; int last;
-  float* z; float* dphi; float* d2phi; long long ldf;
-  __device__ float operator()(int r, int c) const {
-    float zz = split_sum(src, r, c);
-    if (bias) zz += bias[c];
-    const long long o = (long long)r * ldf + c;
-    if (last) { z[o] = zz; return zz; }
-    float a, d1, d2;
-    act_eval(act, zz, a, d1, d2);
-    dphi[o] = d1;
-    if (d2phi) d2phi[o] = d2;
-    return a;
+void launch_convert_batch(Ctx& ctx, Elem elem, ConvertBatch& b) {
+  int blocks = 0;
+  double bytes = 0;
+  for (int i = 0; i < b.n; ++i) {
+    b.block_begin[i] = blocks;
+    blocks += ((b.j[i].cols + 63) / 64) * ((b.j[i].rows + 63) / 64);
+    bytes += (double)b.j[i].rows * b.j[i].cols * (4.0 + ((b.j[i].out ? 1 : 0) + (b.j[i].outT ? 1 : 0)) * elem_size(elem));
   }
-};
-
-void launch_fwd_epilogue(Ctx& ctx, Elem elem, SplitSrc src, const float* bias, int act, bool last,
-                         int rows, int cols, float* z_out, float* dphi, float* d2phi, long long ldf,
-                         void* out, int ld, void* outT, int ldT) {
-  FwdEpi f{src, bias, act, last ? 1 : 0, z_out, dphi, d2phi, ldf};
-  launch_tile_dual(ctx, elem, BETTY_K_EPILOGUE, 0, f, rows, cols, last ? nullptr : out, ld,
-                   last ? nullptr : outT, ldT);
+  b.block_begin[b.n] = blocks;
+  if (blocks <= 0) return;
+  Launch l(ctx, BETTY_K_SHADOW, 0, bytes);
+  if (elem == ELEM_BF16) convert_batch_kernel<__bf16><<<blocks, 256, 0, ctx.stream>>>(b);
+  else convert_batch_kernel<float><<<blocks, 256, 0, ctx.stream>>>(b);
 }
-
-struct BwdEpi {
-  SplitSrc src; const float* dphi; float* e; long long ldf;
-  __device__ float operator()(int r, int c) const {
-    const float t = split_sum(src, r, c);
-    const long long o = (long long)r * ldf + c;
-    if (e) e[o] = t * e[o];
-    return t * dphi[o];
-  }
-};
-
-void launch_bwd_epilogue(Ctx& ctx, Elem elem, SplitSrc src, const float* dphi, float* e,
-                         long long ldf, int rows, int cols, void* out, int ld, void* outT, int ldT) {
-  BwdEpi f{src, dphi, e, ldf};
-  launch_tile_dual(ctx, elem, BETTY_K_EPILOGUE, 0, f, rows, cols, out, ld, outT, ldT);
-}
-
-struct RFwdEpi {
-  SplitSrc src; const float* cb; int last; const float* dphi; float* Rz; long long ldf;
-  __device__ float operator()(int r, int c) const {
-    float rz = split_sum(src, r, c);
-    if (cb) rz += cb[c];
-    const long long o = (long long)r * ldf + c;
-    Rz[o] = rz;
-    return last ? rz : dphi[o] * rz;
-  }
-};
-
-void launch_rfwd_epilogue(Ctx& ctx, Elem elem, SplitSrc src, const float* cb, bool last,
-                          const float* dphi, float* Rz, long long ldf, int rows, int cols, void* out,
-                          int ld, void* outT, int ldT) {
-  RFwdEpi f{src, cb, last ? 1 : 0, dphi, Rz, ldf};
-  launch_tile_dual(ctx, elem, BETTY_K_EPILOGUE, 0, f, rows, cols, last ? nullptr : out, ld,
-                   last ? nullptr : outT, ldT);
-}
-
-struct RBwdEpi {
-  SplitSrc src; const float* dphi; const float* e; const float* Rz; long long ldf;
-  __device__ float operator()(int r, int c) const {
-    const float t = split_sum(src, r, c);
-    const long long o = (long long)r * ldf + c;
-    float out = t * dphi[o];
-    if (e) out += e[o] * Rz[o];
-    return out;
-  }
-};
-
-void launch_rbwd_epilogue(Ctx& ctx, Elem elem, SplitSrc src, const float* dphi, const float* e,
-                          const float* Rz, long long ldf, int rows, int cols, void* out, int ld,
-                          void* outT, int ldT) {
-  RBwdEpi f{src, dphi, e, Rz, ldf};
-  launch_tile_dual(ctx, elem, BETTY_K_EPILOGUE, 0, f, rows, cols, out, ld, outT, ldT);
-}
-
-struct ConvertSrc {
-  const float* src; long long lds; float scale;
-  __device__ float operator()(int r, int c) const { return scale * src[(long long)r * lds + c]; }
-};
 
 void launch_convert_dual(Ctx& ctx, Elem elem, const float* src, long long lds, float scale,
                          int rows, int cols, void* out, int ld, void* outT, int ldT) {
-  ConvertSrc f{src, lds, scale};
-  const double bytes = (double)rows * cols * (4.0 + 2.0 * elem_size(elem));
-  launch_tile_dual(ctx, elem, BETTY_K_SHADOW, bytes, f, rows, cols, out, ld, outT, ldT);
+  ConvertBatch b;
+  b.n = 1;
+  b.j[0] = ConvertJob{src, lds, scale, rows, cols, out, ld, outT, ldT};
+  launch_convert_batch(ctx, elem, b);
 }
 
 // ------------------------------------------------------------------------------------------
 // row-wise loss kernels: one wavefront per sample
 // ------------------------------------------------------------------------------------------
 
+template <typename T>
 __global__ __launch_bounds__(256) void loss_rows_kernel(LossArgs a) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (row >= a.rows) return;
@@ -229,51 +138,72 @@ __global__ __launch_bounds__(256) void loss_rows_kernel(LossArgs a) {
   }
   const float s = omega * a.inv_batch;
   if (lane == 0) { a.ell[row] = ell; a.s[row] = s; a.omega[row] = omega; }
-  float* dz = a.dZ + (long long)row * a.lddz;
+  T* D = (T*)a.D + (long long)row * a.ldD;
+  T* Dt = (T*)a.Dt + row;
   if (a.loss == BETTY_LOSS_SOFTMAX_CE) {
     float* P = a.P + (long long)row * a.ldz;
     const float inv = 1.f / sum;
     for (int c = lane; c < a.C; c += 64) {
       const float p = expf(z[c] - m) * inv;
       P[c] = p;
-      dz[c] = s * (p - (c == y ? 1.f : 0.f));
+      const T dv = from_float<T>(s * (p - (c == y ? 1.f : 0.f)));
+      D[c] = dv;
+      Dt[(long long)c * a.ldDt] = dv;
     }
   } else {
     const float* t = a.target + (long long)row * a.C;
-    for (int c = lane; c < a.C; c += 64) dz[c] = s * 2.f * (z[c] - t[c]);
+    for (int c = lane; c < a.C; c += 64) {
+      const T dv = from_float<T>(s * 2.f * (z[c] - t[c]));
+      D[c] = dv;
+      Dt[(long long)c * a.ldDt] = dv;
+    }
   }
 }
 
-void launch_loss_rows(Ctx& ctx, const LossArgs& a) {
+void launch_loss_rows(Ctx& ctx, Elem elem, const LossArgs& a) {
   if (a.rows <= 0) return;
   Launch l(ctx, BETTY_K_LOSS);
-  loss_rows_kernel<<<(a.rows + 3) / 4, 256, 0, ctx.stream>>>(a);
+  if (elem == ELEM_BF16) loss_rows_kernel<__bf16><<<(a.rows + 3) / 4, 256, 0, ctx.stream>>>(a);
+  else loss_rows_kernel<float><<<(a.rows + 3) / 4, 256, 0, ctx.stream>>>(a);
 }
 
+template <typename T>
 __global__ __launch_bounds__(256) void loss_hessian_rows_kernel(int loss, const float* P, const float* Rz,
                                                                 long long ld, const float* s, int rows,
-                                                                int C, float* out, long long ldo) {
+                                                                int C, T* D, int ldD, T* Dt, int ldDt) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (row >= rows) return;
   const float* rz = Rz + (long long)row * ld;
-  float* o = out + (long long)row * ldo;
+  T* o = D + (long long)row * ldD;
+  T* ot = Dt + row;
   const float si = s[row];
   if (loss == BETTY_LOSS_SOFTMAX_CE) {
     const float* p = P + (long long)row * ld;
     float dot = 0.f;
     for (int c = lane; c < C; c += 64) dot += p[c] * rz[c];
     dot = wave_sum(dot);
-    for (int c = lane; c < C; c += 64) o[c] = si * (p[c] * rz[c] - p[c] * dot);
+    for (int c = lane; c < C; c += 64) {
+      const T v = from_float<T>(si * (p[c] * rz[c] - p[c] * dot));
+      o[c] = v;
+      ot[(long long)c * ldDt] = v;
+    }
   } else {
-    for (int c = lane; c < C; c += 64) o[c] = si * 2.f * rz[c];
+    for (int c = lane; c < C; c += 64) {
+      const T v = from_float<T>(si * 2.f * rz[c]);
+      o[c] = v;
+      ot[(long long)c * ldDt] = v;
+    }
   }
 }
 
-void launch_loss_hessian_rows(Ctx& ctx, int loss, const float* P, const float* Rz, long long ld,
-                              const float* s, int rows, int C, float* out, long long ldo) {
+void launch_loss_hessian_rows(Ctx& ctx, Elem elem, int loss, const float* P, const float* Rz, long long ld,
+                              const float* s, int rows, int C, void* D, int ldD, void* Dt, int ldDt) {
   if (rows <= 0) return;
   Launch l(ctx, BETTY_K_LOSS);
-  loss_hessian_rows_kernel<<<(rows + 3) / 4, 256, 0, ctx.stream>>>(loss, P, Rz, ld, s, rows, C, out, ldo);
+  if (elem == ELEM_BF16)
+    loss_hessian_rows_kernel<__bf16><<<(rows + 3) / 4, 256, 0, ctx.stream>>>(loss, P, Rz, ld, s, rows, C, (__bf16*)D, ldD, (__bf16*)Dt, ldDt);
+  else
+    loss_hessian_rows_kernel<float><<<(rows + 3) / 4, 256, 0, ctx.stream>>>(loss, P, Rz, ld, s, rows, C, (float*)D, ldD, (float*)Dt, ldDt);
 }
 
 __global__ __launch_bounds__(256) void loss_directional_rows_kernel(int loss, const float* P, const float* Z,
@@ -344,26 +274,6 @@ void launch_wnet_theta_vjp(Ctx& ctx, const float* ell, const float* omega, const
   wnet_theta_vjp_kernel<<<hidden + 1, 256, 0, ctx.stream>>>(ell, omega, c, theta, hidden, rows, inv_batch, out);
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void row_sums_kernel(const T* M, int ld, int rows, int k, float* out) {
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (row >= rows) return;
-  const T* p = M + (long long)row * ld;
-  float acc = 0.f;
-  for (int c = lane; c < k; c += 64) acc += to_float(p[c]);
-  acc = wave_sum(acc);
-  if (lane == 0) out[row] = acc;
-}
-
-void launch_row_sums(Ctx& ctx, Elem elem, const void* M, int ld, int rows, int k, float* out) {
-  if (rows <= 0) return;
-  Launch l(ctx, BETTY_K_REDUCE);
-  if (elem == ELEM_BF16)
-    row_sums_kernel<__bf16><<<(rows + 3) / 4, 256, 0, ctx.stream>>>((const __bf16*)M, ld, rows, k, out);
-  else
-    row_sums_kernel<float><<<(rows + 3) / 4, 256, 0, ctx.stream>>>((const float*)M, ld, rows, k, out);
-}
-
 // ------------------------------------------------------------------------------------------
 // streaming kernels over flat vectors
 // ------------------------------------------------------------------------------------------
@@ -387,40 +297,12 @@ void launch_fill_zero(Ctx& ctx, void* p, size_t bytes) {
   fill_zero_kernel<<<flat_grid(bytes / 16), 256, 0, ctx.stream>>>((uint4*)p, bytes / 16);
 }
 
-__global__ __launch_bounds__(256) void copy2_kernel(const float* src, float* a, float* b, size_t n) {
-  FLAT_LOOP(i, n) { const float x = src[i]; a[i] = x; b[i] = x; }
-}
-void launch_copy2(Ctx& ctx, const float* src, float* a, float* b, size_t n) {
-  Launch l(ctx, BETTY_K_VECTOR, 0, 12.0 * n);
-  copy2_kernel<<<flat_grid(n), 256, 0, ctx.stream>>>(src, a, b, n);
-}
-
 __global__ __launch_bounds__(256) void scale_copy_kernel(const float* src, float scale, float* dst, size_t n) {
   FLAT_LOOP(i, n) dst[i] = scale * src[i];
 }
 void launch_scale_copy(Ctx& ctx, const float* src, float scale, float* dst, size_t n) {
   Launch l(ctx, BETTY_K_VECTOR, 0, 8.0 * n);
   scale_copy_kernel<<<flat_grid(n), 256, 0, ctx.stream>>>(src, scale, dst, n);
-}
-
-__global__ __launch_bounds__(256) void add_l2_term_kernel(float* out, const float* lam, const float* x, size_t n) {
-  FLAT_LOOP(i, n) out[i] += 2.f * expf(lam[i]) * x[i];
-}
-void launch_add_l2_term(Ctx& ctx, float* out, const float* lam, const float* x, size_t n) {
-  Launch l(ctx, BETTY_K_VECTOR, 0, 16.0 * n);
-  add_l2_term_kernel<<<flat_grid(n), 256, 0, ctx.stream>>>(out, lam, x, n);
-}
-
-__global__ __launch_bounds__(256) void neumann_update_kernel(float* v, float* p, const float* Hv, float alpha, size_t n) {
-  FLAT_LOOP(i, n) {
-    const float vn = v[i] - alpha * Hv[i];
-    v[i] = vn;
-    p[i] += vn;
-  }
-}
-void launch_neumann_update(Ctx& ctx, float* v, float* p, const float* Hv, float alpha, size_t n) {
-  Launch l(ctx, BETTY_K_VECTOR, 0, 20.0 * n);
-  neumann_update_kernel<<<flat_grid(n), 256, 0, ctx.stream>>>(v, p, Hv, alpha, n);
 }
 
 __global__ __launch_bounds__(256) void mixed_l2_kernel(const float* lam, const float* w, const float* p, float alpha, float* out, size_t n) {
