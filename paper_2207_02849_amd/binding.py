@@ -14,7 +14,8 @@ from typing import Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libbetty_hip.so")
+# BETTY_HIP_LIBRARY overrides the in-tree build (e.g. to try another build of the same ABI)
+LIB_PATH = os.environ.get("BETTY_HIP_LIBRARY") or os.path.join(_HERE, "libbetty_hip.so")
 
 ACT = {"none": 0, "relu": 1, "gelu": 2}
 LOSS = {"mse": 0, "ce": 1}

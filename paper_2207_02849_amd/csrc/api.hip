@@ -73,11 +73,9 @@ struct betty_handle_s {
   bool bound = false, batches = false;
   betty_batch batch[2]{};
   OperandSet sets[2];        // [0]: element type of desc.prec; [1]: fp32 set for finite differences when prec is bf16
-  size_t scratch = 0;        // fp32 GEMM output / split-K partials
-  int s_max = 16;
   size_t vec_g = 0, vec_v = 0, vec_p = 0, vec_Hv = 0, vec_wpm = 0, vec_Gm = 0;
-  size_t partials = 0, scalars = 0, tickets = 0;
-  int tune_target_blocks = 512, tune_tile128_min = 128;   // see plan_chain
+  size_t partials = 0, scalars = 0;
+  int tune_target_blocks = 256, tune_tile128_min = 192;   // see plan_chain
 
   template <typename T = void> T* at(size_t off) const { return (T*)(ws + off); }
   float* f(size_t off) const { return (float*)(ws + off); }
@@ -163,11 +161,9 @@ void plan(betty_handle h) {
   const Elem main_elem = h->desc.prec == BETTY_PREC_BF16_FP32ACC ? ELEM_BF16 : ELEM_F32;
   plan_set(h, pl, h->sets[0], main_elem);
   if (main_elem == ELEM_BF16) plan_set(h, pl, h->sets[1], ELEM_F32);
-  h->scratch = pl.take((size_t)h->s_max * h->max_Bp * h->max_np * 4);
   const size_t vb = h->d * 4;
   h->vec_g = pl.take(vb); h->vec_v = pl.take(vb); h->vec_p = pl.take(vb); h->vec_Hv = pl.take(vb);
   h->vec_wpm = pl.take(vb); h->vec_Gm = pl.take(vb);
-  h->tickets = pl.take((size_t)(h->max_Bp / 64) * (h->max_np / 64) * 4);
   h->partials = pl.take(1024 * 8);
   h->scalars = pl.take(256);
   h->ws_need = pl.off;
@@ -175,21 +171,17 @@ void plan(betty_handle h) {
 
 OperandSet& fd_operands(betty_handle h) { return h->sets[1].present ? h->sets[1] : h->sets[0]; }
 
-// Tile shape and K-split of an activation-shaped GEMM (M = batch): aim at about two workgroups
-// per compute unit, never fewer than two k-tiles per slice.
-struct ChainPlan { int tile, S; };
-
-ChainPlan plan_chain(betty_handle h, Elem elem, int Mp, int Np, int Ktot_p) {
-  ChainPlan cp;
+// Kernel configuration of an activation-shaped GEMM (M = batch): full 128-tiles when there are
+// enough of them to fill the chip, otherwise 64-tiles; K is split inside the workgroup when the
+// launch would still leave most compute units idle and K is long enough to share.
+int plan_chain(betty_handle h, Elem elem, int Mp, int Np, int Ktot_p) {
   const int tiles128 = (Mp / 128) * (Np / 128);
-  cp.tile = tiles128 >= h->tune_tile128_min ? TILE_128 : TILE_64;
-  const int tiles = cp.tile == TILE_128 ? tiles128 : 4 * tiles128;
   const int TT = Ktot_p / gemm_ktile_elems(elem);
-  int S = (h->tune_target_blocks + tiles - 1) / tiles;
-  S = std::min(S, h->s_max);
-  S = std::min(S, std::max(1, TT / 2));
-  cp.S = std::max(S, 1);
-  return cp;
+  if (tiles128 >= h->tune_tile128_min) return GEMM_128x1;
+  if (tiles128 >= h->tune_tile128_min / 2 && TT >= 8) return GEMM_128x2;
+  const int tiles64 = 4 * tiles128;
+  if (tiles64 < h->tune_target_blocks && TT >= 8) return GEMM_64x4;
+  return GEMM_64x1;
 }
 
 void set_pairs(GemmArgs& g, const void* A0, int lda0, const void* B0, int ldb0, int K0p, const void* A1,
@@ -205,17 +197,11 @@ void chain_gemm(betty_handle h, Elem elem, const void* A0, int lda0, const void*
                 const Epilogue& e, double flops) {
   GemmBatch b;
   b.n = 1;
-  b.partials = h->f(h->scratch);
-  b.tickets = h->at<int>(h->tickets);
   GemmProblem& p = b.p[0];
   set_pairs(p.g, A0, lda0, B0, ldb0, K0p, A1, lda1, B1, ldb1, K1p);
   p.g.M = M; p.g.N = N; p.g.Mp = Mp; p.g.Np = Np;
-  const ChainPlan cp = plan_chain(h, elem, Mp, Np, p.g.Kp[0] + p.g.Kp[1]);
-  p.g.splitk = cp.S;
   p.e = e;
-  p.partial_base = 0;
-  p.ticket_base = 0;
-  launch_gemm_batch(h->ctx, elem, cp.tile, b, flops);
+  launch_gemm_batch(h->ctx, elem, plan_chain(h, elem, Mp, Np, p.g.Kp[0] + p.g.Kp[1]), b, flops);
 }
 
 Epilogue blank_epilogue(int mode, int act = 0) {
@@ -337,8 +323,6 @@ void wgrad_batch(betty_handle h, OperandSet& os, int side, bool rop, const Wgrad
   const int L = h->L, B = sb.B, Bp = sb.Bp;
   for (int l0 = 1; l0 <= L; l0 += MAX_PROBLEMS) {
     GemmBatch b;
-    b.partials = h->f(h->scratch);
-    b.tickets = h->at<int>(h->tickets);
     b.n = std::min(MAX_PROBLEMS, L - l0 + 1);
     double flops = 0;
     for (int i = 0; i < b.n; ++i) {
@@ -357,8 +341,7 @@ void wgrad_batch(betty_handle h, OperandSet& os, int side, bool rop, const Wgrad
                   h->at<void>(os.RDt[l]), Bp, Bp);
         flops += 4.0 * B * li.n_in * li.n_out;
       }
-      p.g.M = li.n_in; p.g.N = li.n_out; p.g.Mp = li.n_in_p; p.g.Np = li.n_out_p; p.g.splitk = 1;
-      p.partial_base = 0; p.ticket_base = 0;
+      p.g.M = li.n_in; p.g.N = li.n_out; p.g.Mp = li.n_in_p; p.g.Np = li.n_out_p;
       Epilogue e = blank_epilogue(k.mode);
       e.ldc = li.n_out;
       e.C = k.C ? k.C + li.w_off : nullptr;
@@ -384,7 +367,7 @@ void wgrad_batch(betty_handle h, OperandSet& os, int side, bool rop, const Wgrad
         j.alpha = k.alpha;
       }
     }
-    launch_gemm_batch(h->ctx, os.elem, TILE_128, b, flops);
+    launch_gemm_batch(h->ctx, os.elem, GEMM_128x1, b, flops);
   }
 }
 

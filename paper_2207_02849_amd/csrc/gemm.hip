@@ -9,13 +9,15 @@
 // of the R-op passes, e.g. Rz = Ra W + a V as [Ra | a] [W ; V].
 //
 // Launch = a batch of up to MAX_PROBLEMS independent problems plus optional bias-row jobs,
-// flattened on blockIdx.x.  A problem may be split along K into S slices; the S workgroups of a
-// tile write their accumulators to a partials buffer in register order, and the last one to
-// arrive (an atomic ticket per tile, no spinning) re-reads all S slices in slice order - so the
-// sum is bit-reproducible - and runs the epilogue.  The ticket is reset by that workgroup.
+// flattened on blockIdx.x.  Skinny problems (few output tiles, long K) are split along K *inside*
+// the workgroup: KG groups of 4 wavefronts each take a contiguous range of k-tiles with their own
+// LDS operand buffers, and the groups' accumulators are summed through LDS in group order, so the
+// result is bit-reproducible and no inter-workgroup synchronisation exists.  (Splitting K across
+// workgroups was measured first: the agent-scope fences it needs write back the L2 of every XCD
+// and cost 10-80 us per launch on this chip.)
 //
-// Tiling: 256 threads (4 wavefronts, 2 x 2) own a BM x BN tile; a wavefront owns TM x TN MFMA
-// blocks of 32 x 32.  K is consumed in tiles of NCH 16-byte chunks per row: global -> registers
+// Tiling: 4 wavefronts (2 x 2) own a BM x BN tile; a wavefront owns TM x TN MFMA blocks of
+// 32 x 32.  K is consumed in tiles of NCH 16-byte chunks per row: global -> registers
 // -> LDS with the next tile's global loads in flight during the multiplies.  LDS rows are padded
 // by one chunk so the 16-byte fragment reads of 8 consecutive rows hit distinct banks.
 //
@@ -31,18 +33,19 @@ namespace betty {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte chunk
 
 template <typename T> struct MfmaChunk;
 
 template <> struct MfmaChunk<__bf16> {
-  static __device__ __forceinline__ void run(const uint4& a, const uint4& b, f32x16& acc) {
+  static __device__ __forceinline__ void run(const u32x4& a, const u32x4& b, f32x16& acc) {
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
                                                   acc, 0, 0, 0);
   }
 };
 
 template <> struct MfmaChunk<float> {
-  static __device__ __forceinline__ void run(const uint4& a, const uint4& b, f32x16& acc) {
+  static __device__ __forceinline__ void run(const u32x4& a, const u32x4& b, f32x16& acc) {
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
@@ -82,33 +85,37 @@ template <> __device__ __forceinline__ void store4<__bf16>(__bf16* p, const floa
   *(bf16x4*)p = v;
 }
 
-// One register quad: rows row0..row0+3 (row0 % 4 == 0) of column col.  M, N = valid extent.
-template <typename T>
-__device__ __forceinline__ void epilogue_quad(const Epilogue& e, int M, int N, int row0, int col,
-                                              const float (&acc)[4]) {
-  if (col >= N || row0 >= M) return;
-  float val[4];
-  bool dual = true;
-  switch (e.mode) {
-    case EPI_STORE: {
+// One 32x32 MFMA block as seen by one lane: 16 accumulators = rows rb + 8*(k/4) + k%4 (k = 0..15)
+// of column col, with rb = block row + 4*(lane/32).  M, N = valid extent.  Every mode first issues
+// all of its loads for the 16 elements, then computes, then stores, so that the memory latency is
+// paid once per block and not once per element.
+template <typename T, int MODE>
+__device__ __forceinline__ void epilogue_block(const Epilogue& e, int M, int N, int rb, int col,
+                                               const f32x16 acc) {
+  if (col >= N || rb >= M) return;
+  bool ok[16];
+  long long of[16];      // offset into the fp32 side arrays (ldf) or the flat slice (ldc)
+  const long long ldx = MODE >= EPI_WGRAD ? e.ldc : e.ldf;
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
-        if (row0 + k < M) e.C[(long long)(row0 + k) * e.ldc + col] = acc[k];
-      return;
-    }
+  for (int k = 0; k < 16; ++k) {
+    const int row = rb + 8 * (k >> 2) + (k & 3);
+    ok[k] = row < M;
+    of[k] = (long long)row * ldx + col;
+  }
+  float val[16];
+  switch (MODE) {
     case EPI_FWD: {
       const float b = e.colvec ? e.colvec[col] : 0.f;
+      float d1[16], d2[16];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        val[k] = 0.f;
-        if (row0 + k < M) {
-          const long long o = (long long)(row0 + k) * e.ldf + col;
-          float a, d1, d2;
-          act_eval(e.act, acc[k] + b, a, d1, d2);
-          e.dphi_out[o] = d1;
-          if (e.d2_out) e.d2_out[o] = d2;
-          val[k] = a;
-        }
+      for (int k = 0; k < 16; ++k) act_eval(e.act, acc[k] + b, val[k], d1[k], d2[k]);
+#pragma unroll
+      for (int k = 0; k < 16; ++k)
+        if (ok[k]) e.dphi_out[of[k]] = d1[k];
+      if (e.d2_out) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+          if (ok[k]) e.d2_out[of[k]] = d2[k];
       }
       break;
     }
@@ -116,103 +123,117 @@ __device__ __forceinline__ void epilogue_quad(const Epilogue& e, int M, int N, i
     case EPI_RFWD_LAST: {
       const float b = e.colvec ? e.colvec[col] : 0.f;
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
-        if (row0 + k < M) e.f0[(long long)(row0 + k) * e.ldf + col] = acc[k] + b;
+      for (int k = 0; k < 16; ++k)
+        if (ok[k]) e.f0[of[k]] = acc[k] + b;
       return;
     }
     case EPI_BWD: {
+      float dp[16], ee[16];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        val[k] = 0.f;
-        if (row0 + k < M) {
-          const long long o = (long long)(row0 + k) * e.ldf + col;
-          if (e.e_io) e.e_io[o] = acc[k] * e.e_io[o];
-          val[k] = acc[k] * e.dphi[o];
-        }
+      for (int k = 0; k < 16; ++k) dp[k] = ok[k] ? e.dphi[of[k]] : 0.f;
+      if (e.e_io) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) ee[k] = ok[k] ? e.e_io[of[k]] : 0.f;
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+          if (ok[k]) e.e_io[of[k]] = acc[k] * ee[k];
       }
+#pragma unroll
+      for (int k = 0; k < 16; ++k) val[k] = acc[k] * dp[k];
       break;
     }
     case EPI_RFWD: {
       const float b = e.colvec ? e.colvec[col] : 0.f;
+      float dp[16];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        val[k] = 0.f;
-        if (row0 + k < M) {
-          const long long o = (long long)(row0 + k) * e.ldf + col;
-          const float rz = acc[k] + b;
-          e.f0[o] = rz;
-          val[k] = e.dphi[o] * rz;
-        }
-      }
+      for (int k = 0; k < 16; ++k) dp[k] = ok[k] ? e.dphi[of[k]] : 0.f;
+#pragma unroll
+      for (int k = 0; k < 16; ++k)
+        if (ok[k]) e.f0[of[k]] = acc[k] + b;
+#pragma unroll
+      for (int k = 0; k < 16; ++k) val[k] = dp[k] * (acc[k] + b);
       break;
     }
     case EPI_RBWD: {
+      float dp[16], ee[16], rz[16];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        val[k] = 0.f;
-        if (row0 + k < M) {
-          const long long o = (long long)(row0 + k) * e.ldf + col;
-          float r = acc[k] * e.dphi[o];
-          if (e.e) r += e.e[o] * e.Rz[o];
-          val[k] = r;
-        }
+      for (int k = 0; k < 16; ++k) dp[k] = ok[k] ? e.dphi[of[k]] : 0.f;
+      if (e.e) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) { ee[k] = ok[k] ? e.e[of[k]] : 0.f; rz[k] = ok[k] ? e.Rz[of[k]] : 0.f; }
+      } else {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) { ee[k] = 0.f; rz[k] = 0.f; }
       }
+#pragma unroll
+      for (int k = 0; k < 16; ++k) val[k] = acc[k] * dp[k] + ee[k] * rz[k];
       break;
     }
     case EPI_WGRAD: {             // C = acc (+ 2 e^lam x)
+      float lm[16], xx[16];
+      if (e.lam) {
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
-        if (row0 + k < M) {
-          const long long o = (long long)(row0 + k) * e.ldc + col;
-          float gval = acc[k];
-          if (e.lam) gval += 2.f * expf(e.lam[o]) * e.x[o];
-          e.C[o] = gval;
-        }
+        for (int k = 0; k < 16; ++k) { lm[k] = ok[k] ? e.lam[of[k]] : 0.f; xx[k] = ok[k] ? e.x[of[k]] : 0.f; }
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+          if (ok[k]) e.C[of[k]] = acc[k] + 2.f * expf(lm[k]) * xx[k];
+      } else {
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+          if (ok[k]) e.C[of[k]] = acc[k];
+      }
       return;
     }
     case EPI_WGRAD_INIT: {        // v = p = acc ; operand copies of v
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        val[k] = 0.f;
-        if (row0 + k < M) {
-          const long long o = (long long)(row0 + k) * e.ldc + col;
-          e.v[o] = acc[k];
-          e.p[o] = acc[k];
-          val[k] = acc[k];
-        }
+      for (int k = 0; k < 16; ++k) {
+        val[k] = ok[k] ? acc[k] : 0.f;
+        if (ok[k]) { e.v[of[k]] = acc[k]; e.p[of[k]] = acc[k]; }
       }
-      dual = e.out != nullptr;
       break;
     }
     case EPI_WGRAD_NEUMANN: {     // Hv = acc (+ 2 e^lam v); v <- v - alpha Hv; p <- p + v; copies of v
+      float vo[16], po[16], lm[16];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        val[k] = 0.f;
-        if (row0 + k < M) {
-          const long long o = (long long)(row0 + k) * e.ldc + col;
-          const float vo = e.v[o];
-          float hv = acc[k];
-          if (e.lam) hv += 2.f * expf(e.lam[o]) * vo;
-          const float vn = vo - e.alpha * hv;
-          e.v[o] = vn;
-          e.p[o] += vn;
-          val[k] = vn;
-        }
+      for (int k = 0; k < 16; ++k) { vo[k] = ok[k] ? e.v[of[k]] : 0.f; po[k] = ok[k] ? e.p[of[k]] : 0.f; }
+      if (e.lam) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) lm[k] = ok[k] ? e.lam[of[k]] : 0.f;
       }
-      dual = e.out != nullptr;
+#pragma unroll
+      for (int k = 0; k < 16; ++k) {
+        float hv = acc[k];
+        if (e.lam) hv += 2.f * expf(lm[k]) * vo[k];
+        val[k] = ok[k] ? vo[k] - e.alpha * hv : 0.f;
+      }
+#pragma unroll
+      for (int k = 0; k < 16; ++k)
+        if (ok[k]) { e.v[of[k]] = val[k]; e.p[of[k]] = po[k] + val[k]; }
       break;
     }
     default:
       return;
   }
-  if (!dual) return;
+  // operand-typed copies: row-major element by element, transposed as 4-element vectors
+  if (MODE != EPI_WGRAD_INIT && MODE != EPI_WGRAD_NEUMANN) {
+#pragma unroll
+    for (int k = 0; k < 16; ++k)
+      if (!ok[k]) val[k] = 0.f;
+  }
   if (e.out) {
     T* o = (T*)e.out;
 #pragma unroll
-    for (int k = 0; k < 4; ++k)
-      if (row0 + k < M) store1<T>(o + (long long)(row0 + k) * e.ld + col, val[k]);
+    for (int k = 0; k < 16; ++k)
+      if (ok[k]) store1<T>(o + (long long)(rb + 8 * (k >> 2) + (k & 3)) * e.ld + col, val[k]);
   }
-  if (e.outT) store4<T>((T*)e.outT + (long long)col * e.ldT + row0, val);
+  if (e.outT) {
+    T* o = (T*)e.outT + (long long)col * e.ldT + rb;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float quad[4] = {val[4 * q], val[4 * q + 1], val[4 * q + 2], val[4 * q + 3]};
+      if (rb + 8 * q < M) store4<T>(o + 8 * q, quad);
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -226,16 +247,16 @@ __device__ __forceinline__ float wave_sum_f(float x) {
 }
 
 // bias-shaped outputs: one wavefront per row of a K-major matrix, same update rules as the tiles
-template <typename T>
-__device__ void bias_rows(const BiasJob& j, int local_block) {
-  const int row = local_block * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+template <typename T, int MODE>
+__device__ void bias_rows(const BiasJob& j, int row) {
+  const int lane = threadIdx.x & 63;
   if (row >= j.rows) return;
   const T* p = (const T*)j.Mt + (long long)row * j.ld;
   float acc = 0.f;
   for (int c = lane; c < j.k; c += 64) acc += (float)p[c];
   acc = wave_sum_f(acc);
   if (lane != 0) return;
-  switch (j.mode) {
+  switch (MODE) {
     case EPI_WGRAD: {
       float g = acc;
       if (j.lam) g += 2.f * expf(j.lam[row]) * j.x[row];
@@ -258,8 +279,8 @@ __device__ void bias_rows(const BiasJob& j, int local_block) {
   }
 }
 
-template <typename T, int BM, int BN, int NCH>
-__global__ __launch_bounds__(256) void gemm_fused_kernel(GemmBatch batch) {
+template <typename T, int BM, int BN, int NCH, int KG, int MODE>
+__global__ __launch_bounds__(256 * KG) void gemm_fused_kernel(GemmBatch batch) {
   constexpr int ROW = NCH + 1;                     // LDS row pitch in 16-byte chunks
   constexpr int EPC = 16 / (int)sizeof(T);         // elements per chunk
   constexpr int KT = NCH * EPC;                    // elements per k-tile
@@ -267,12 +288,13 @@ __global__ __launch_bounds__(256) void gemm_fused_kernel(GemmBatch batch) {
   constexpr int LA = BM * NCH / 256, LB = BN * NCH / 256;
   constexpr int NACC = TM * TN * 16;
   static_assert(BM % 64 == 0 && BN % 64 == 0 && (BM * NCH) % 256 == 0 && (BN * NCH) % 256 == 0, "tile");
-  __shared__ uint4 sA[BM * ROW];
-  __shared__ uint4 sB[BN * ROW];
-  __shared__ int s_last;
+  extern __shared__ u32x4 smem[];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // KG groups of 4 wavefronts share the tile; group kg owns a contiguous range of k-tiles
+  const int kg = threadIdx.x >> 8, tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
+  u32x4* sA = smem + kg * ((BM + BN) * ROW);
+  u32x4* sB = sA + BM * ROW;
 
   // ---- which job is this workgroup?
   int bid = blockIdx.x;
@@ -280,165 +302,200 @@ __global__ __launch_bounds__(256) void gemm_fused_kernel(GemmBatch batch) {
     bid -= batch.gemm_blocks;
     int j = 0;
     while (j + 1 < batch.n_bias && bid >= batch.bias_begin[j + 1]) ++j;
-    bias_rows<T>(batch.bias[j], bid - batch.bias_begin[j]);
+    bias_rows<T, MODE>(batch.bias[j], (bid - batch.bias_begin[j]) * (4 * KG) + (threadIdx.x >> 6));
     return;
   }
   int pi = 0;
   while (pi + 1 < batch.n && bid >= batch.block_begin[pi + 1]) ++pi;
   const GemmArgs& g = batch.p[pi].g;
-  const int local = bid - batch.block_begin[pi];
-  const int S = g.splitk;
-  const int tile = local / S, s = local - tile * S;
+  const int tile = bid - batch.block_begin[pi];
   const int tiles_n = g.Np / BN;
   const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
 
   const int T0 = g.Kp[0] / KT, T1 = g.Kp[1] / KT, TT = T0 + T1;
-  const int tb = (int)((long long)TT * s / S);
-  const int te = (int)((long long)TT * (s + 1) / S);
+  const int NI = (TT + KG - 1) / KG;               // iterations of every group (same barrier count)
+  const int tb = kg * NI;
+  const int te = tb + NI < TT ? tb + NI : TT;
 
-  f32x16 acc[TM][TN];
+  f32x16 acc[TM * TN];
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < TM * TN; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
 
-  uint4 ra[LA], rb[LB];
-  auto gload = [&](int t) {
-    const int pair = t >= T0 ? 1 : 0;
-    const int tt = pair ? t - T0 : t;
-    const T* Ab = (const T*)g.A[pair];
-    const T* Bb = (const T*)g.B[pair];
-    const long long lda = g.lda[pair], ldb = g.ldb[pair];
-#pragma unroll
-    for (int i = 0; i < LA; ++i) {
-      const int idx = tid + i * 256, r = idx / NCH, c = idx % NCH;
-      ra[i] = *(const uint4*)(Ab + (long long)(m0 + r) * lda + (long long)tt * KT + c * EPC);
-    }
-#pragma unroll
-    for (int i = 0; i < LB; ++i) {
-      const int idx = tid + i * 256, r = idx / NCH, c = idx % NCH;
-      rb[i] = *(const uint4*)(Bb + (long long)(n0 + r) * ldb + (long long)tt * KT + c * EPC);
-    }
-  };
-
-  if (tb < te) gload(tb);
-  for (int t = tb; t < te; ++t) {
-    if (t > tb) __syncthreads();
-#pragma unroll
-    for (int i = 0; i < LA; ++i) {
-      const int idx = tid + i * 256;
-      sA[(idx / NCH) * ROW + idx % NCH] = ra[i];
-    }
-#pragma unroll
-    for (int i = 0; i < LB; ++i) {
-      const int idx = tid + i * 256;
-      sB[(idx / NCH) * ROW + idx % NCH] = rb[i];
-    }
-    __syncthreads();
-    if (t + 1 < te) gload(t + 1);
-#pragma unroll
-    for (int j = 0; j < NCH / 2; ++j) {
-      const int c = 2 * j + (lane >> 5);
-      uint4 af[TM], bf[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = sA[(wm * TM * 32 + i * 32 + (lane & 31)) * ROW + c];
-#pragma unroll
-      for (int i = 0; i < TN; ++i) bf[i] = sB[(wn * TN * 32 + i * 32 + (lane & 31)) * ROW + c];
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int jn = 0; jn < TN; ++jn) MfmaChunk<T>::run(af[i], bf[jn], acc[i][jn]);
-    }
+  u32x4 ra[LA], rb[LB];
+#define BETTY_GLOAD(t_)                                                                              \
+  {                                                                                                  \
+    const int pair_ = (t_) >= T0 ? 1 : 0;                                                            \
+    const int tt_ = pair_ ? (t_) - T0 : (t_);                                                        \
+    const T* Ab_ = (const T*)g.A[pair_] + (long long)m0 * g.lda[pair_] + (long long)tt_ * KT;        \
+    const T* Bb_ = (const T*)g.B[pair_] + (long long)n0 * g.ldb[pair_] + (long long)tt_ * KT;        \
+    const long long lda_ = g.lda[pair_], ldb_ = g.ldb[pair_];                                        \
+    _Pragma("unroll") for (int i_ = 0; i_ < LA; ++i_) {                                              \
+      const int idx_ = tid + i_ * 256;                                                               \
+      ra[i_] = *(const u32x4*)(Ab_ + (long long)(idx_ / NCH) * lda_ + (idx_ % NCH) * EPC);           \
+    }                                                                                                \
+    _Pragma("unroll") for (int i_ = 0; i_ < LB; ++i_) {                                              \
+      const int idx_ = tid + i_ * 256;                                                               \
+      rb[i_] = *(const u32x4*)(Bb_ + (long long)(idx_ / NCH) * ldb_ + (idx_ % NCH) * EPC);           \
+    }                                                                                                \
   }
 
-  // ---- split-K: publish this slice; the last workgroup of the tile sums all slices in order
-  if (S > 1) {
-    float* part = batch.partials + ((long long)(batch.p[pi].partial_base + (long long)tile * S)) * (NACC * 256);
-    float* mine = part + (long long)s * (NACC * 256) + tid;
+  if (tb < te) BETTY_GLOAD(tb)
+  for (int it = 0; it < NI; ++it) {
+    const int t = tb + it;
+    if (it > 0) __syncthreads();
+    if (t < te) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < LA; ++i) {
+        const int idx = tid + i * 256;
+        sA[(idx / NCH) * ROW + idx % NCH] = ra[i];
+      }
 #pragma unroll
-      for (int jn = 0; jn < TN; ++jn)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mine[((i * TN + jn) * 16 + r) * 256] = acc[i][jn][r];
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-      int* ticket = batch.tickets + batch.p[pi].ticket_base + tile;
-      const int old = atomicAdd(ticket, 1);
-      const int last = old == S - 1;
-      if (last) *ticket = 0;
-      s_last = last;
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int jn = 0; jn < TN; ++jn)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][jn][r] = 0.f;
-    for (int s2 = 0; s2 < S; ++s2) {
-      const float* src = part + (long long)s2 * (NACC * 256) + tid;
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int jn = 0; jn < TN; ++jn)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[i][jn][r] += src[((i * TN + jn) * 16 + r) * 256];
-    }
-  }
-
-  // ---- epilogue from registers
-  const Epilogue& e = batch.p[pi].e;
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int jn = 0; jn < TN; ++jn) {
-      const int col = n0 + wn * TN * 32 + jn * 32 + (lane & 31);
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int row0 = m0 + wm * TM * 32 + i * 32 + 8 * q + 4 * (lane >> 5);
-        const float quad[4] = {acc[i][jn][4 * q], acc[i][jn][4 * q + 1], acc[i][jn][4 * q + 2], acc[i][jn][4 * q + 3]};
-        epilogue_quad<T>(e, g.M, g.N, row0, col, quad);
+      for (int i = 0; i < LB; ++i) {
+        const int idx = tid + i * 256;
+        sB[(idx / NCH) * ROW + idx % NCH] = rb[i];
       }
     }
+    __syncthreads();
+    if (t + 1 < te) BETTY_GLOAD(t + 1)
+    if (t < te) {
+#pragma unroll
+      for (int j = 0; j < NCH / 2; ++j) {
+        const int c = 2 * j + (lane >> 5);
+        u32x4 af[TM], bf[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[i] = sA[(wm * TM * 32 + i * 32 + (lane & 31)) * ROW + c];
+#pragma unroll
+        for (int i = 0; i < TN; ++i) bf[i] = sB[(wn * TN * 32 + i * 32 + (lane & 31)) * ROW + c];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int jn = 0; jn < TN; ++jn) MfmaChunk<T>::run(af[i], bf[jn], acc[i * TN + jn]);
+      }
+    }
+  }
+#undef BETTY_GLOAD
+
+  // ---- combine the K groups through LDS in group order (bit-reproducible); group 0 finishes
+  if constexpr (KG > 1) {
+    __syncthreads();                                // all groups are done with the operand tiles
+    float* red = (float*)smem;
+    if (kg > 0) {
+#pragma unroll
+      for (int i = 0; i < TM * TN; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[(((kg - 1) * TM * TN + i) * 16 + r) * 256 + tid] = acc[i][r];
+    }
+    __syncthreads();
+    if (kg > 0) return;
+    for (int g2 = 1; g2 < KG; ++g2) {
+#pragma unroll
+      for (int i = 0; i < TM * TN; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] += red[(((g2 - 1) * TM * TN + i) * 16 + r) * 256 + tid];
+    }
+  }
+
+  // ---- epilogue from registers, one MFMA block at a time
+  const Epilogue& e = batch.p[pi].e;
+#pragma unroll
+  for (int ij = 0; ij < TM * TN; ++ij)
+    epilogue_block<T, MODE>(e, g.M, g.N, m0 + wm * TM * 32 + (ij / TN) * 32 + 4 * (lane >> 5),
+                            n0 + wn * TN * 32 + (ij % TN) * 32 + (lane & 31), acc[ij]);
 }
 
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
 
-int gemm_ktile_elems(Elem elem) { return GEMM_NCH * (elem == ELEM_BF16 ? 8 : 4); }
+template <typename T, int BT, int KG>
+constexpr size_t lds_bytes() {
+  constexpr size_t operands = (size_t)KG * 2 * BT * (GEMM_NCH + 1) * 16;
+  constexpr size_t reduce = (size_t)(KG - 1) * BT * BT * 4;
+  return operands > reduce ? operands : reduce;
+}
 
-void launch_gemm_batch(Ctx& ctx, Elem elem, int tile, GemmBatch& b, double flops) {
-  const int bt = tile == TILE_128 ? 128 : 64;
+template <typename T, int BT, int KG, int MODE>
+static void launch_one(int total, hipStream_t st, const GemmBatch& b, hipError_t& err) {
+  constexpr size_t lds = lds_bytes<T, BT, KG>();
+  static bool configured = false;
+  if (!configured) {
+    if (lds > 48 * 1024) {
+      hipError_t e = hipFuncSetAttribute((const void*)gemm_fused_kernel<T, BT, BT, GEMM_NCH, KG, MODE>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) { err = e; return; }
+    }
+    configured = true;
+  }
+  gemm_fused_kernel<T, BT, BT, GEMM_NCH, KG, MODE><<<total, 256 * KG, lds, st>>>(b);
+}
+
+template <typename T, int BT, int KG>
+static void launch_chain_mode(int mode, int total, hipStream_t st, const GemmBatch& b, hipError_t& err) {
+  switch (mode) {
+#define BETTY_CASE(M_) case M_: launch_one<T, BT, KG, M_>(total, st, b, err); break;
+    BETTY_CASE(EPI_FWD) BETTY_CASE(EPI_FWD_LAST) BETTY_CASE(EPI_BWD) BETTY_CASE(EPI_RFWD)
+    BETTY_CASE(EPI_RFWD_LAST) BETTY_CASE(EPI_RBWD)
+    default: err = hipErrorInvalidValue; break;
+  }
+}
+
+template <typename T, int BT>
+static void launch_wgrad_mode(int mode, int total, hipStream_t st, const GemmBatch& b, hipError_t& err) {
+  switch (mode) {
+#define BETTY_CASE_W(M_) case M_: launch_one<T, BT, 1, M_>(total, st, b, err); break;
+    BETTY_CASE_W(EPI_WGRAD) BETTY_CASE_W(EPI_WGRAD_INIT) BETTY_CASE_W(EPI_WGRAD_NEUMANN)
+#undef BETTY_CASE_W
+    default: err = hipErrorInvalidValue; break;
+  }
+}
+#undef BETTY_CASE
+
+template <typename T>
+static void launch_elem(int cfg, int mode, int total, hipStream_t st, const GemmBatch& b, hipError_t& err) {
+  if (mode >= EPI_WGRAD) {
+    if (cfg == GEMM_128x1) launch_wgrad_mode<T, 128>(mode, total, st, b, err);
+    else if (cfg == GEMM_64x1) launch_wgrad_mode<T, 64>(mode, total, st, b, err);
+    else err = hipErrorInvalidValue;
+    return;
+  }
+  switch (cfg) {
+    case GEMM_128x1: launch_chain_mode<T, 128, 1>(mode, total, st, b, err); break;
+    case GEMM_128x2: launch_chain_mode<T, 128, 2>(mode, total, st, b, err); break;
+    case GEMM_64x1: launch_chain_mode<T, 64, 1>(mode, total, st, b, err); break;
+    case GEMM_64x4: launch_chain_mode<T, 64, 4>(mode, total, st, b, err); break;
+    default: err = hipErrorInvalidValue; break;
+  }
+}
+
+int gemm_ktile_elems(Elem elem) { return GEMM_NCH * (elem == ELEM_BF16 ? 8 : 4); }
+int gemm_cfg_tile(int cfg) { return (cfg == GEMM_128x1 || cfg == GEMM_128x2) ? 128 : 64; }
+int gemm_cfg_groups(int cfg) { return cfg == GEMM_128x2 ? 2 : cfg == GEMM_64x4 ? 4 : 1; }
+
+void launch_gemm_batch(Ctx& ctx, Elem elem, int cfg, GemmBatch& b, double flops) {
+  const int bt = gemm_cfg_tile(cfg);
+  const int rows_per_block = 4 * gemm_cfg_groups(cfg);
   int blocks = 0;
   for (int i = 0; i < b.n; ++i) {
     b.block_begin[i] = blocks;
-    blocks += (b.p[i].g.Mp / bt) * (b.p[i].g.Np / bt) * b.p[i].g.splitk;
+    blocks += (b.p[i].g.Mp / bt) * (b.p[i].g.Np / bt);
   }
   b.block_begin[b.n] = blocks;
   b.gemm_blocks = blocks;
   int bias_blocks = 0;
   for (int i = 0; i < b.n_bias; ++i) {
     b.bias_begin[i] = bias_blocks;
-    bias_blocks += (b.bias[i].rows + 3) / 4;
+    bias_blocks += (b.bias[i].rows + rows_per_block - 1) / rows_per_block;
   }
   b.bias_begin[b.n_bias] = bias_blocks;
   const int total = blocks + bias_blocks;
   if (total <= 0) return;
   Launch l(ctx, BETTY_K_GEMM, flops, 0);
-  if (elem == ELEM_BF16) {
-    if (tile == TILE_128) gemm_fused_kernel<__bf16, 128, 128, GEMM_NCH><<<total, 256, 0, ctx.stream>>>(b);
-    else gemm_fused_kernel<__bf16, 64, 64, GEMM_NCH><<<total, 256, 0, ctx.stream>>>(b);
-  } else {
-    if (tile == TILE_128) gemm_fused_kernel<float, 128, 128, GEMM_NCH><<<total, 256, 0, ctx.stream>>>(b);
-    else gemm_fused_kernel<float, 64, 64, GEMM_NCH><<<total, 256, 0, ctx.stream>>>(b);
-  }
+  hipError_t err = hipSuccess;
+  if (elem == ELEM_BF16) launch_elem<__bf16>(cfg, b.p[0].e.mode, total, ctx.stream, b, err);
+  else launch_elem<float>(cfg, b.p[0].e.mode, total, ctx.stream, b, err);
+  if (err != hipSuccess && ctx.first_error == hipSuccess) ctx.first_error = err;
 }
 
 }  // namespace betty

@@ -30,13 +30,11 @@ struct GemmArgs {
   int Kp[2];                 // padded reduction extents in elements; 0 = pair absent
   int M, N;                  // valid output extent (epilogue stores are bounds-checked against it)
   int Mp, Np;                // padded extents (define the tile grid)
-  int splitk;                // number of K slices per tile
 };
 
 // What happens to a finished accumulator tile.
 enum EpiMode {
-  EPI_STORE = 0,         // C[row][col] = acc
-  EPI_FWD,               // z = acc + bias; out = phi(z); dphi_out = phi'(z); d2_out = phi''(z)
+  EPI_FWD = 1,             // z = acc + bias; out = phi(z); dphi_out = phi'(z); d2_out = phi''(z)
   EPI_FWD_LAST,          // f0 = acc + bias                       (logits)
   EPI_BWD,               // out = acc * dphi; e_io = acc * e_io   (delta of the layer below)
   EPI_RFWD,              // f0 = rz = acc + cbias; out = dphi * rz
@@ -61,7 +59,7 @@ struct Epilogue {
   float* v; float* p; float alpha;
 };
 
-struct GemmProblem { GemmArgs g; Epilogue e; long long partial_base; int ticket_base; };
+struct GemmProblem { GemmArgs g; Epilogue e; };
 
 // out[row] from sum_k Mt[row][k]: bias-shaped slices of the WGRAD modes
 struct BiasJob {
@@ -71,14 +69,13 @@ struct BiasJob {
 
 constexpr int MAX_PROBLEMS = 8;
 constexpr int GEMM_NCH = 8;              // 16-byte chunks per row of a k-tile
-enum { TILE_128 = 0, TILE_64 = 1 };
+// tile extent x number of K groups per workgroup
+enum { GEMM_128x1 = 0, GEMM_128x2 = 1, GEMM_64x1 = 2, GEMM_64x4 = 3 };
 
 struct GemmBatch {
   int n = 0, n_bias = 0, gemm_blocks = 0;
   int block_begin[MAX_PROBLEMS + 1];
   int bias_begin[MAX_PROBLEMS + 1];
-  float* partials = nullptr;             // split-K slices, (tile, slice, register, thread) order
-  int* tickets = nullptr;                // one arrival counter per tile, zero between launches
   GemmProblem p[MAX_PROBLEMS];
   BiasJob bias[MAX_PROBLEMS];
 };
@@ -103,7 +100,8 @@ struct Launch {   // RAII bracket around one kernel launch
 
 // ---- gemm.hip
 int gemm_ktile_elems(Elem elem);
-void launch_gemm_batch(Ctx& ctx, Elem elem, int tile, GemmBatch& batch, double algorithmic_flops);
+int gemm_cfg_tile(int cfg);
+void launch_gemm_batch(Ctx& ctx, Elem elem, int cfg, GemmBatch& batch, double algorithmic_flops);
 
 // ---- kernels.hip : operand conversion -----------------------------------------------------
 // out (row-major [rows_p][ld]) and outT ([cols_p][ldT]) = convert(scale * src[r * lds + c]); either may be null
