@@ -279,22 +279,28 @@ __device__ void bias_rows(const BiasJob& j, int row) {
   }
 }
 
-template <typename T, int BM, int BN, int NCH, int KG, int MODE>
-__global__ __launch_bounds__(256 * KG) void gemm_fused_kernel(GemmBatch batch) {
+template <typename T, int BM, int BN, int NCH, int WPG, int KG, int MODE>
+__global__ __launch_bounds__(64 * WPG * KG) void gemm_fused_kernel(GemmBatch batch) {
+  constexpr int GT = 64 * WPG;                     // threads of one K group
+  constexpr int WM = WPG == 4 ? 2 : 1, WN = WPG == 4 ? 2 : 1;   // wavefronts of a group over the tile
   constexpr int ROW = NCH + 1;                     // LDS row pitch in 16-byte chunks
   constexpr int EPC = 16 / (int)sizeof(T);         // elements per chunk
   constexpr int KT = NCH * EPC;                    // elements per k-tile
-  constexpr int TM = BM / 64, TN = BN / 64;        // 32x32 blocks per wavefront
-  constexpr int LA = BM * NCH / 256, LB = BN * NCH / 256;
-  constexpr int NACC = TM * TN * 16;
-  static_assert(BM % 64 == 0 && BN % 64 == 0 && (BM * NCH) % 256 == 0 && (BN * NCH) % 256 == 0, "tile");
+  constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);   // 32x32 blocks per wavefront
+  constexpr int LA = BM * NCH / GT, LB = BN * NCH / GT;
+  static_assert(WPG == 1 || WPG == 4, "a K group is one wavefront or 2 x 2 wavefronts");
+  static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0 && (BM * NCH) % GT == 0 && (BN * NCH) % GT == 0, "tile");
   extern __shared__ u32x4 smem[];
 
-  // KG groups of 4 wavefronts share the tile; group kg owns a contiguous range of k-tiles
-  const int kg = threadIdx.x >> 8, tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  // KG groups share the tile; group kg owns a contiguous range of k-tiles and its own LDS
+  // operand buffers.  (Wavefront-uniform values are forced into scalar registers.)
+  const int kg = __builtin_amdgcn_readfirstlane(threadIdx.x / GT);
+  const int tid = threadIdx.x % GT, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = WPG == 4 ? wave >> 1 : 0, wn = WPG == 4 ? wave & 1 : 0;
   u32x4* sA = smem + kg * ((BM + BN) * ROW);
   u32x4* sB = sA + BM * ROW;
+  // a one-wavefront group owns its LDS region alone: no workgroup barrier inside the k loop
+#define BETTY_GROUP_SYNC() do { if constexpr (WPG == 1) __builtin_amdgcn_wave_barrier(); else __syncthreads(); } while (0)
 
   // ---- which job is this workgroup?
   int bid = blockIdx.x;
@@ -302,7 +308,7 @@ __global__ __launch_bounds__(256 * KG) void gemm_fused_kernel(GemmBatch batch) {
     bid -= batch.gemm_blocks;
     int j = 0;
     while (j + 1 < batch.n_bias && bid >= batch.bias_begin[j + 1]) ++j;
-    bias_rows<T, MODE>(batch.bias[j], (bid - batch.bias_begin[j]) * (4 * KG) + (threadIdx.x >> 6));
+    bias_rows<T, MODE>(batch.bias[j], (bid - batch.bias_begin[j]) * (WPG * KG) + (threadIdx.x >> 6));
     return;
   }
   int pi = 0;
@@ -323,59 +329,67 @@ __global__ __launch_bounds__(256 * KG) void gemm_fused_kernel(GemmBatch batch) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
 
-  u32x4 ra[LA], rb[LB];
-#define BETTY_GLOAD(t_)                                                                              \
+  // Two register sets hold the global loads of the next two k-tiles, so two tiles' worth of
+  // loads are in flight while a third is multiplied out of LDS.
+  u32x4 ra0[LA], rb0[LB], ra1[LA], rb1[LB];
+  // operand bases of both pairs are read from the kernel arguments once, not per k-tile
+  const long long lda0 = g.lda[0], lda1 = g.lda[1], ldb0 = g.ldb[0], ldb1 = g.ldb[1];
+  const T* const Abase0 = (const T*)g.A[0] + (long long)m0 * lda0 + (long long)(tid / NCH) * lda0 + (tid % NCH) * EPC;
+  const T* const Abase1 = (const T*)g.A[1] + (long long)m0 * lda1 + (long long)(tid / NCH) * lda1 + (tid % NCH) * EPC;
+  const T* const Bbase0 = (const T*)g.B[0] + (long long)n0 * ldb0 + (long long)(tid / NCH) * ldb0 + (tid % NCH) * EPC;
+  const T* const Bbase1 = (const T*)g.B[1] + (long long)n0 * ldb1 + (long long)(tid / NCH) * ldb1 + (tid % NCH) * EPC;
+#define BETTY_GLOAD(RA_, RB_, t_)                                                                    \
   {                                                                                                  \
-    const int pair_ = (t_) >= T0 ? 1 : 0;                                                            \
-    const int tt_ = pair_ ? (t_) - T0 : (t_);                                                        \
-    const T* Ab_ = (const T*)g.A[pair_] + (long long)m0 * g.lda[pair_] + (long long)tt_ * KT;        \
-    const T* Bb_ = (const T*)g.B[pair_] + (long long)n0 * g.ldb[pair_] + (long long)tt_ * KT;        \
-    const long long lda_ = g.lda[pair_], ldb_ = g.ldb[pair_];                                        \
-    _Pragma("unroll") for (int i_ = 0; i_ < LA; ++i_) {                                              \
-      const int idx_ = tid + i_ * 256;                                                               \
-      ra[i_] = *(const u32x4*)(Ab_ + (long long)(idx_ / NCH) * lda_ + (idx_ % NCH) * EPC);           \
+    const bool second_ = (t_) >= T0;                                                                 \
+    const int tt_ = second_ ? (t_) - T0 : (t_);                                                      \
+    const T* Ab_ = (second_ ? Abase1 : Abase0) + (long long)tt_ * KT;                                \
+    const T* Bb_ = (second_ ? Bbase1 : Bbase0) + (long long)tt_ * KT;                                \
+    const long long lda_ = (second_ ? lda1 : lda0) * (GT / NCH);                                    \
+    const long long ldb_ = (second_ ? ldb1 : ldb0) * (GT / NCH);                                    \
+    _Pragma("unroll") for (int i_ = 0; i_ < LA; ++i_) RA_[i_] = *(const u32x4*)(Ab_ + i_ * lda_);    \
+    _Pragma("unroll") for (int i_ = 0; i_ < LB; ++i_) RB_[i_] = *(const u32x4*)(Bb_ + i_ * ldb_);    \
+  }
+  // one k-tile: registers -> LDS, refill the registers two tiles ahead, multiply.  Every thread
+  // of the workgroup passes both barriers whether or not its group still has a tile (t_ < te).
+#define BETTY_STAGE(RA_, RB_, t_, first_)                                                            \
+  {                                                                                                  \
+    if (!(first_)) BETTY_GROUP_SYNC();                                                               \
+    if ((t_) < te) {                                                                                 \
+      _Pragma("unroll") for (int i_ = 0; i_ < LA; ++i_) {                                            \
+        const int idx_ = tid + i_ * GT;                                                              \
+        sA[(idx_ / NCH) * ROW + idx_ % NCH] = RA_[i_];                                               \
+      }                                                                                              \
+      _Pragma("unroll") for (int i_ = 0; i_ < LB; ++i_) {                                            \
+        const int idx_ = tid + i_ * GT;                                                              \
+        sB[(idx_ / NCH) * ROW + idx_ % NCH] = RB_[i_];                                               \
+      }                                                                                              \
     }                                                                                                \
-    _Pragma("unroll") for (int i_ = 0; i_ < LB; ++i_) {                                              \
-      const int idx_ = tid + i_ * 256;                                                               \
-      rb[i_] = *(const u32x4*)(Bb_ + (long long)(idx_ / NCH) * ldb_ + (idx_ % NCH) * EPC);           \
+    BETTY_GROUP_SYNC();                                                                              \
+    if ((t_) + 2 < te) BETTY_GLOAD(RA_, RB_, (t_) + 2)                                               \
+    if ((t_) < te) {                                                                                 \
+      _Pragma("unroll") for (int j_ = 0; j_ < NCH / 2; ++j_) {                                       \
+        const int c_ = 2 * j_ + (lane >> 5);                                                         \
+        u32x4 af_[TM], bf_[TN];                                                                      \
+        _Pragma("unroll") for (int i_ = 0; i_ < TM; ++i_)                                            \
+          af_[i_] = sA[(wm * TM * 32 + i_ * 32 + (lane & 31)) * ROW + c_];                           \
+        _Pragma("unroll") for (int i_ = 0; i_ < TN; ++i_)                                            \
+          bf_[i_] = sB[(wn * TN * 32 + i_ * 32 + (lane & 31)) * ROW + c_];                           \
+        _Pragma("unroll") for (int i_ = 0; i_ < TM; ++i_)                                            \
+          _Pragma("unroll") for (int jn_ = 0; jn_ < TN; ++jn_)                                       \
+            MfmaChunk<T>::run(af_[i_], bf_[jn_], acc[i_ * TN + jn_]);                                \
+      }                                                                                              \
     }                                                                                                \
   }
 
-  if (tb < te) BETTY_GLOAD(tb)
-  for (int it = 0; it < NI; ++it) {
-    const int t = tb + it;
-    if (it > 0) __syncthreads();
-    if (t < te) {
-#pragma unroll
-      for (int i = 0; i < LA; ++i) {
-        const int idx = tid + i * 256;
-        sA[(idx / NCH) * ROW + idx % NCH] = ra[i];
-      }
-#pragma unroll
-      for (int i = 0; i < LB; ++i) {
-        const int idx = tid + i * 256;
-        sB[(idx / NCH) * ROW + idx % NCH] = rb[i];
-      }
-    }
-    __syncthreads();
-    if (t + 1 < te) BETTY_GLOAD(t + 1)
-    if (t < te) {
-#pragma unroll
-      for (int j = 0; j < NCH / 2; ++j) {
-        const int c = 2 * j + (lane >> 5);
-        u32x4 af[TM], bf[TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) af[i] = sA[(wm * TM * 32 + i * 32 + (lane & 31)) * ROW + c];
-#pragma unroll
-        for (int i = 0; i < TN; ++i) bf[i] = sB[(wn * TN * 32 + i * 32 + (lane & 31)) * ROW + c];
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int jn = 0; jn < TN; ++jn) MfmaChunk<T>::run(af[i], bf[jn], acc[i * TN + jn]);
-      }
-    }
+  if (tb < te) BETTY_GLOAD(ra0, rb0, tb)
+  if (tb + 1 < te) BETTY_GLOAD(ra1, rb1, tb + 1)
+  for (int it = 0; it < NI; it += 2) {
+    BETTY_STAGE(ra0, rb0, tb + it, it == 0)
+    if (it + 1 < NI) BETTY_STAGE(ra1, rb1, tb + it + 1, false)
   }
+#undef BETTY_STAGE
 #undef BETTY_GLOAD
+#undef BETTY_GROUP_SYNC
 
   // ---- combine the K groups through LDS in group order (bit-reproducible); group 0 finishes
   if constexpr (KG > 1) {
@@ -385,15 +399,16 @@ __global__ __launch_bounds__(256 * KG) void gemm_fused_kernel(GemmBatch batch) {
 #pragma unroll
       for (int i = 0; i < TM * TN; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) red[(((kg - 1) * TM * TN + i) * 16 + r) * 256 + tid] = acc[i][r];
+        for (int r = 0; r < 16; ++r) red[(((kg - 1) * TM * TN + i) * 16 + r) * GT + tid] = acc[i][r];
     }
     __syncthreads();
     if (kg > 0) return;
+#pragma unroll 1
     for (int g2 = 1; g2 < KG; ++g2) {
 #pragma unroll
       for (int i = 0; i < TM * TN; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] += red[(((g2 - 1) * TM * TN + i) * 16 + r) * 256 + tid];
+        for (int r = 0; r < 16; ++r) acc[i][r] += red[(((g2 - 1) * TM * TN + i) * 16 + r) * GT + tid];
     }
   }
 
@@ -409,32 +424,32 @@ __global__ __launch_bounds__(256 * KG) void gemm_fused_kernel(GemmBatch batch) {
 // host side
 // ------------------------------------------------------------------------------------------
 
-template <typename T, int BT, int KG>
+template <typename T, int BT, int WPG, int KG>
 constexpr size_t lds_bytes() {
   constexpr size_t operands = (size_t)KG * 2 * BT * (GEMM_NCH + 1) * 16;
   constexpr size_t reduce = (size_t)(KG - 1) * BT * BT * 4;
   return operands > reduce ? operands : reduce;
 }
 
-template <typename T, int BT, int KG, int MODE>
+template <typename T, int BT, int WPG, int KG, int MODE>
 static void launch_one(int total, hipStream_t st, const GemmBatch& b, hipError_t& err) {
-  constexpr size_t lds = lds_bytes<T, BT, KG>();
+  constexpr size_t lds = lds_bytes<T, BT, WPG, KG>();
   static bool configured = false;
   if (!configured) {
     if (lds > 48 * 1024) {
-      hipError_t e = hipFuncSetAttribute((const void*)gemm_fused_kernel<T, BT, BT, GEMM_NCH, KG, MODE>,
+      hipError_t e = hipFuncSetAttribute((const void*)gemm_fused_kernel<T, BT, BT, GEMM_NCH, WPG, KG, MODE>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (e != hipSuccess) { err = e; return; }
     }
     configured = true;
   }
-  gemm_fused_kernel<T, BT, BT, GEMM_NCH, KG, MODE><<<total, 256 * KG, lds, st>>>(b);
+  gemm_fused_kernel<T, BT, BT, GEMM_NCH, WPG, KG, MODE><<<total, 64 * WPG * KG, lds, st>>>(b);
 }
 
-template <typename T, int BT, int KG>
+template <typename T, int BT, int WPG, int KG>
 static void launch_chain_mode(int mode, int total, hipStream_t st, const GemmBatch& b, hipError_t& err) {
   switch (mode) {
-#define BETTY_CASE(M_) case M_: launch_one<T, BT, KG, M_>(total, st, b, err); break;
+#define BETTY_CASE(M_) case M_: launch_one<T, BT, WPG, KG, M_>(total, st, b, err); break;
     BETTY_CASE(EPI_FWD) BETTY_CASE(EPI_FWD_LAST) BETTY_CASE(EPI_BWD) BETTY_CASE(EPI_RFWD)
     BETTY_CASE(EPI_RFWD_LAST) BETTY_CASE(EPI_RBWD)
     default: err = hipErrorInvalidValue; break;
@@ -444,7 +459,7 @@ static void launch_chain_mode(int mode, int total, hipStream_t st, const GemmBat
 template <typename T, int BT>
 static void launch_wgrad_mode(int mode, int total, hipStream_t st, const GemmBatch& b, hipError_t& err) {
   switch (mode) {
-#define BETTY_CASE_W(M_) case M_: launch_one<T, BT, 1, M_>(total, st, b, err); break;
+#define BETTY_CASE_W(M_) case M_: launch_one<T, BT, 4, 1, M_>(total, st, b, err); break;
     BETTY_CASE_W(EPI_WGRAD) BETTY_CASE_W(EPI_WGRAD_INIT) BETTY_CASE_W(EPI_WGRAD_NEUMANN)
 #undef BETTY_CASE_W
     default: err = hipErrorInvalidValue; break;
@@ -461,21 +476,22 @@ static void launch_elem(int cfg, int mode, int total, hipStream_t st, const Gemm
     return;
   }
   switch (cfg) {
-    case GEMM_128x1: launch_chain_mode<T, 128, 1>(mode, total, st, b, err); break;
-    case GEMM_128x2: launch_chain_mode<T, 128, 2>(mode, total, st, b, err); break;
-    case GEMM_64x1: launch_chain_mode<T, 64, 1>(mode, total, st, b, err); break;
-    case GEMM_64x4: launch_chain_mode<T, 64, 4>(mode, total, st, b, err); break;
+    case GEMM_128x1: launch_chain_mode<T, 128, 4, 1>(mode, total, st, b, err); break;
+    case GEMM_128x2: launch_chain_mode<T, 128, 4, 2>(mode, total, st, b, err); break;
+    case GEMM_64x1: launch_chain_mode<T, 64, 4, 1>(mode, total, st, b, err); break;
+    case GEMM_64x4: launch_chain_mode<T, 64, 4, 4>(mode, total, st, b, err); break;
+    case GEMM_32x16: launch_chain_mode<T, 32, 1, 16>(mode, total, st, b, err); break;
     default: err = hipErrorInvalidValue; break;
   }
 }
 
 int gemm_ktile_elems(Elem elem) { return GEMM_NCH * (elem == ELEM_BF16 ? 8 : 4); }
-int gemm_cfg_tile(int cfg) { return (cfg == GEMM_128x1 || cfg == GEMM_128x2) ? 128 : 64; }
-int gemm_cfg_groups(int cfg) { return cfg == GEMM_128x2 ? 2 : cfg == GEMM_64x4 ? 4 : 1; }
+int gemm_cfg_tile(int cfg) { return (cfg == GEMM_128x1 || cfg == GEMM_128x2) ? 128 : cfg == GEMM_32x16 ? 32 : 64; }
+static int gemm_cfg_waves(int cfg) { return cfg == GEMM_128x2 ? 8 : cfg == GEMM_64x4 ? 16 : cfg == GEMM_32x16 ? 16 : 4; }
 
 void launch_gemm_batch(Ctx& ctx, Elem elem, int cfg, GemmBatch& b, double flops) {
   const int bt = gemm_cfg_tile(cfg);
-  const int rows_per_block = 4 * gemm_cfg_groups(cfg);
+  const int rows_per_block = gemm_cfg_waves(cfg);
   int blocks = 0;
   for (int i = 0; i < b.n; ++i) {
     b.block_begin[i] = blocks;
