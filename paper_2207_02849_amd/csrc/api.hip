@@ -76,6 +76,7 @@ struct betty_handle_s {
   size_t vec_g = 0, vec_v = 0, vec_p = 0, vec_Hv = 0, vec_wpm = 0, vec_Gm = 0;
   size_t partials = 0, scalars = 0;
   int tune_target_blocks = 256, tune_tile128_min = 192;   // see plan_chain
+  int tune_wgrad_cfg = GEMM_64x1;
 
   template <typename T = void> T* at(size_t off) const { return (T*)(ws + off); }
   float* f(size_t off) const { return (float*)(ws + off); }
@@ -174,8 +175,7 @@ OperandSet& fd_operands(betty_handle h) { return h->sets[1].present ? h->sets[1]
 // Kernel configuration of an activation-shaped GEMM (M = batch): full 128-tiles when there are
 // enough of them to fill the chip, otherwise 64-tiles; K is split inside the workgroup when the
 // launch would still leave most compute units idle and K is long enough to share.
-int plan_chain(betty_handle h, Elem elem, int Mp, int Np, int Ktot_p) {
-  const int tiles128 = (Mp / 128) * (Np / 128);
+int plan_chain(betty_handle h, Elem elem, int tiles128, int Ktot_p) {
   const int TT = Ktot_p / gemm_ktile_elems(elem);
   if (tiles128 >= h->tune_tile128_min) return GEMM_128x1;
   if (tiles128 >= h->tune_tile128_min / 2 && TT >= 8) return GEMM_128x2;
@@ -202,7 +202,7 @@ void chain_gemm(betty_handle h, Elem elem, const void* A0, int lda0, const void*
   set_pairs(p.g, A0, lda0, B0, ldb0, K0p, A1, lda1, B1, ldb1, K1p);
   p.g.M = M; p.g.N = N; p.g.Mp = Mp; p.g.Np = Np;
   p.e = e;
-  launch_gemm_batch(h->ctx, elem, plan_chain(h, elem, Mp, Np, p.g.Kp[0] + p.g.Kp[1]), b, flops);
+  launch_gemm_batch(h->ctx, elem, plan_chain(h, elem, (Mp / 128) * (Np / 128), p.g.Kp[0] + p.g.Kp[1]), b, flops);
 }
 
 Epilogue blank_epilogue(int mode, int act = 0) {
@@ -244,66 +244,105 @@ void make_weight_operands(betty_handle h, OperandSet& os, const float* w) {
   if (hybrid_forward(h, os)) make_shadows(h, h->sets[1], w, 1.f, nullptr, &h->sets[1].Wt);
 }
 
+// Which batches a pass covers: the train (lower) side, the validation (upper) side, or both in
+// the same launches (same weights, two independent problems per launch).
+enum { SIDE_TRAIN = 1, SIDE_VAL = 2, SIDE_BOTH = 3 };
+inline bool has_side(int mask, int side) { return (mask >> side) & 1; }
+
 // a_l, phi'(z_l) (and phi'' on the lower side), logits, per-sample loss, output delta
-void forward_and_loss(betty_handle h, OperandSet& os, int side, const float* w, const float* theta) {
-  SideBuf& sb = os.side[side];
-  const int L = h->L, B = sb.B, Bp = sb.Bp;
-  const bool lower = side == 0;
+void forward_and_loss(betty_handle h, OperandSet& os, int sides, const float* w, const float* theta) {
+  const int L = h->L;
   const bool hybrid = hybrid_forward(h, os);
   OperandSet& fs = hybrid ? h->sets[1] : os;          // operands of the forward products
-  SideBuf& fb = fs.side[side];
   for (int l = 1; l <= L; ++l) {
     const LayerInfo& li = h->layers[l - 1];
     const bool last = l == L;
-    const void* Aop = l == 1 ? h->at<void>(fb.X) : h->at<void>(fb.A[l - 1]);
-    Epilogue e = blank_epilogue(last ? EPI_FWD_LAST : EPI_FWD, h->desc.act);
-    e.colvec = h->desc.has_bias ? w + li.b_off : nullptr;
-    e.ldf = li.n_out_p;
-    if (last) {
-      e.f0 = h->f(sb.ZL);
-    } else {
-      e.dphi_out = h->f(sb.dphi[l]);
-      e.d2_out = sb.e2[l] ? h->f(sb.e2[l]) : nullptr;
-      e.out = h->at<void>(fb.A[l]); e.ld = li.n_out_p;
-      e.outT = hybrid ? nullptr : h->at<void>(fb.At[l]); e.ldT = Bp;
+    GemmBatch b;
+    double flops = 0;
+    int tiles128 = 0;
+    for (int side = 0; side < 2; ++side) {
+      if (!has_side(sides, side)) continue;
+      SideBuf& sb = os.side[side];
+      SideBuf& fb = fs.side[side];
+      GemmProblem& p = b.p[b.n++];
+      const void* Aop = l == 1 ? h->at<void>(fb.X) : h->at<void>(fb.A[l - 1]);
+      set_pairs(p.g, Aop, li.n_in_p, h->at<void>(fs.Wt[l - 1]), li.n_in_p, li.n_in_p, nullptr, 0, nullptr, 0, 0);
+      p.g.M = sb.B; p.g.N = li.n_out; p.g.Mp = sb.Bp; p.g.Np = li.n_out_p;
+      Epilogue e = blank_epilogue(last ? EPI_FWD_LAST : EPI_FWD, h->desc.act);
+      e.colvec = h->desc.has_bias ? w + li.b_off : nullptr;
+      e.ldf = li.n_out_p;
+      if (last) {
+        e.f0 = h->f(sb.ZL);
+      } else {
+        e.dphi_out = h->f(sb.dphi[l]);
+        e.d2_out = sb.e2[l] ? h->f(sb.e2[l]) : nullptr;
+        e.out = h->at<void>(fb.A[l]); e.ld = li.n_out_p;
+        e.outT = hybrid ? nullptr : h->at<void>(fb.At[l]); e.ldT = sb.Bp;
+      }
+      p.e = e;
+      flops += 2.0 * sb.B * li.n_in * li.n_out;
+      tiles128 += (sb.Bp / 128) * (li.n_out_p / 128);
     }
-    chain_gemm(h, fs.elem, Aop, li.n_in_p, h->at<void>(fs.Wt[l - 1]), li.n_in_p, li.n_in_p, nullptr, 0, nullptr,
-               0, 0, B, li.n_out, Bp, li.n_out_p, e, 2.0 * B * li.n_in * li.n_out);
-    if (hybrid && !last)
-      launch_convert_dual(h->ctx, os.elem, h->f(fb.A[l]), li.n_out_p, 1.f, B, li.n_out, h->at<void>(sb.A[l]),
-                          li.n_out_p, h->at<void>(sb.At[l]), Bp);
+    launch_gemm_batch(h->ctx, fs.elem, plan_chain(h, fs.elem, tiles128, li.n_in_p), b, flops);
+    if (hybrid && !last) {
+      ConvertBatch cb;
+      for (int side = 0; side < 2; ++side) {
+        if (!has_side(sides, side)) continue;
+        SideBuf& sb = os.side[side];
+        cb.j[cb.n++] = ConvertJob{h->f(fs.side[side].A[l]), li.n_out_p, 1.f, sb.B, li.n_out,
+                                  h->at<void>(sb.A[l]), li.n_out_p, h->at<void>(sb.At[l]), sb.Bp};
+      }
+      launch_convert_batch(h->ctx, os.elem, cb);
+    }
   }
-  (void)lower;
   const LayerInfo& lo = h->layers[L - 1];
-  LossArgs a{};
-  a.loss = h->desc.loss;
-  a.reweight = (side == 0 && h->desc.hp == BETTY_HP_REWEIGHT_NET) ? 1 : 0;
-  a.hidden = h->desc.wnet_hidden;
-  a.Z = h->f(sb.ZL); a.ldz = lo.n_out_p;
-  a.y = h->batch[side].y; a.target = h->batch[side].target; a.C = lo.n_out;
-  a.theta = theta;
-  a.rows = B; a.inv_batch = 1.0f / (float)B;
-  a.ell = h->f(sb.ell); a.s = h->f(sb.s); a.omega = h->f(sb.omega);
-  a.P = h->f(sb.P);
-  a.D = h->at<void>(sb.D[L]); a.ldD = lo.n_out_p;
-  a.Dt = h->at<void>(sb.Dt[L]); a.ldDt = Bp;
-  launch_loss_rows(h->ctx, os.elem, a);
+  LossBatch lb;
+  for (int side = 0; side < 2; ++side) {
+    if (!has_side(sides, side)) continue;
+    SideBuf& sb = os.side[side];
+    LossArgs& a = lb.a[lb.n++];
+    a = LossArgs{};
+    a.loss = h->desc.loss;
+    a.reweight = (side == 0 && h->desc.hp == BETTY_HP_REWEIGHT_NET) ? 1 : 0;
+    a.hidden = h->desc.wnet_hidden;
+    a.Z = h->f(sb.ZL); a.ldz = lo.n_out_p;
+    a.y = h->batch[side].y; a.target = h->batch[side].target; a.C = lo.n_out;
+    a.theta = theta;
+    a.rows = sb.B; a.inv_batch = 1.0f / (float)sb.B;
+    a.ell = h->f(sb.ell); a.s = h->f(sb.s); a.omega = h->f(sb.omega);
+    a.P = h->f(sb.P);
+    a.D = h->at<void>(sb.D[L]); a.ldD = lo.n_out_p;
+    a.Dt = h->at<void>(sb.Dt[L]); a.ldDt = sb.Bp;
+  }
+  launch_loss_rows(h->ctx, os.elem, lb);
 }
 
 // delta_l for every layer below the output (and (delta W^T) phi'' on the lower side)
-void backward_chain(betty_handle h, OperandSet& os, int side) {
-  SideBuf& sb = os.side[side];
-  const int L = h->L, B = sb.B, Bp = sb.Bp;
+void backward_chain(betty_handle h, OperandSet& os, int sides) {
+  const int L = h->L;
   for (int l = L; l >= 2; --l) {
     const LayerInfo& li = h->layers[l - 1];
-    Epilogue e = blank_epilogue(EPI_BWD);
-    e.dphi = h->f(sb.dphi[l - 1]);
-    e.e_io = sb.e2[l - 1] ? h->f(sb.e2[l - 1]) : nullptr;
-    e.ldf = li.n_in_p;
-    e.out = h->at<void>(sb.D[l - 1]); e.ld = li.n_in_p;
-    e.outT = h->at<void>(sb.Dt[l - 1]); e.ldT = Bp;
-    chain_gemm(h, os.elem, h->at<void>(sb.D[l]), li.n_out_p, h->at<void>(os.Wn[l - 1]), li.n_out_p, li.n_out_p,
-               nullptr, 0, nullptr, 0, 0, B, li.n_in, Bp, li.n_in_p, e, 2.0 * B * li.n_in * li.n_out);
+    GemmBatch b;
+    double flops = 0;
+    int tiles128 = 0;
+    for (int side = 0; side < 2; ++side) {
+      if (!has_side(sides, side)) continue;
+      SideBuf& sb = os.side[side];
+      GemmProblem& p = b.p[b.n++];
+      set_pairs(p.g, h->at<void>(sb.D[l]), li.n_out_p, h->at<void>(os.Wn[l - 1]), li.n_out_p, li.n_out_p, nullptr, 0,
+                nullptr, 0, 0);
+      p.g.M = sb.B; p.g.N = li.n_in; p.g.Mp = sb.Bp; p.g.Np = li.n_in_p;
+      Epilogue e = blank_epilogue(EPI_BWD);
+      e.dphi = h->f(sb.dphi[l - 1]);
+      e.e_io = sb.e2[l - 1] ? h->f(sb.e2[l - 1]) : nullptr;
+      e.ldf = li.n_in_p;
+      e.out = h->at<void>(sb.D[l - 1]); e.ld = li.n_in_p;
+      e.outT = h->at<void>(sb.Dt[l - 1]); e.ldT = sb.Bp;
+      p.e = e;
+      flops += 2.0 * sb.B * li.n_in * li.n_out;
+      tiles128 += (sb.Bp / 128) * (li.n_in_p / 128);
+    }
+    launch_gemm_batch(h->ctx, os.elem, plan_chain(h, os.elem, tiles128, li.n_out_p), b, flops);
   }
 }
 
@@ -368,7 +407,7 @@ void wgrad_batch(betty_handle h, OperandSet& os, int side, bool rop, const Wgrad
         j.alpha = k.alpha;
       }
     }
-    launch_gemm_batch(h->ctx, os.elem, GEMM_128x1, b, flops);
+    launch_gemm_batch(h->ctx, os.elem, h->tune_wgrad_cfg, b, flops);
   }
 }
 
@@ -429,8 +468,8 @@ void hvp_cached(betty_handle h, OperandSet& os, const float* vflat, const WgradS
 void lower_grad_seq(betty_handle h, OperandSet& os, const float* w, const float* lam, float* grad,
                     float* loss_or_null) {
   const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
-  forward_and_loss(h, os, 0, w, l2 ? nullptr : lam);
-  backward_chain(h, os, 0);
+  forward_and_loss(h, os, SIDE_TRAIN, w, l2 ? nullptr : lam);
+  backward_chain(h, os, SIDE_TRAIN);
   WgradSink k{EPI_WGRAD, grad, l2 ? lam : nullptr, l2 ? w : nullptr, nullptr, nullptr, 0.f, false};
   wgrad_batch(h, os, 0, false, k);
   if (loss_or_null) {
@@ -443,10 +482,14 @@ void lower_grad_seq(betty_handle h, OperandSet& os, const float* w, const float*
   }
 }
 
-// gradient of the upper cost on the validation batch; the result goes where `sink` says
-void upper_grad_seq(betty_handle h, OperandSet& os, const float* w, const WgradSink& sink, float* loss_or_null) {
-  forward_and_loss(h, os, 1, w, nullptr);
-  backward_chain(h, os, 1);
+// gradient of the upper cost on the validation batch; the result goes where `sink` says.  With
+// with_lower the same launches also build the forward/backward cache of the train batch that the
+// R-op passes need (no parameter gradient on that side).
+void upper_grad_seq(betty_handle h, OperandSet& os, const float* w, const float* lam, bool with_lower,
+                    const WgradSink& sink, float* loss_or_null) {
+  const int sides = with_lower ? SIDE_BOTH : SIDE_VAL;
+  forward_and_loss(h, os, sides, w, h->desc.hp == BETTY_HP_L2_DECAY ? nullptr : lam);
+  backward_chain(h, os, sides);
   wgrad_batch(h, os, 1, false, sink);
   if (loss_or_null)
     launch_weighted_loss_sum(h->ctx, h->f(os.side[1].s), h->f(os.side[1].ell), os.side[1].B, nullptr, loss_or_null);
@@ -454,8 +497,8 @@ void upper_grad_seq(betty_handle h, OperandSet& os, const float* w, const WgradS
 
 // forward/backward cache of the train batch for the R-op passes (no parameter gradient)
 void prepare_lower(betty_handle h, OperandSet& os, const float* w, const float* lam) {
-  forward_and_loss(h, os, 0, w, h->desc.hp == BETTY_HP_L2_DECAY ? nullptr : lam);
-  backward_chain(h, os, 0);
+  forward_and_loss(h, os, SIDE_TRAIN, w, h->desc.hp == BETTY_HP_L2_DECAY ? nullptr : lam);
+  backward_chain(h, os, SIDE_TRAIN);
 }
 
 // out = -(1/B) sum_i c_i dR/dtheta with c_i = <grad_w l_i, scale * qflat>
@@ -624,7 +667,7 @@ betty_status betty_upper_grad(betty_handle h, const float* w, float* grad_w, flo
   OperandSet& os = h->sets[0];
   make_weight_operands(h, os, w);
   WgradSink k{EPI_WGRAD, grad_w, nullptr, nullptr, nullptr, nullptr, 0.f, false};
-  upper_grad_seq(h, os, w, k, loss_or_null);
+  upper_grad_seq(h, os, w, nullptr, false, k, loss_or_null);
   return finish(h);
 }
 
@@ -658,7 +701,7 @@ betty_status betty_mixed_vjp(betty_handle h, const float* w, const float* lambda
   }
   OperandSet& os = h->sets[0];
   make_weight_operands(h, os, w);
-  forward_and_loss(h, os, 0, w, lambda);
+  forward_and_loss(h, os, SIDE_TRAIN, w, lambda);
   mixed_reweight_seq(h, os, lambda, q, 1.f, out);
   return finish(h);
 }
@@ -683,15 +726,24 @@ betty_status betty_hypergrad_neumann(betty_handle h, const float* w, const float
   make_weight_operands(h, os, w);
   // g = grad_w L_U lands directly in v and p, with the operand copies of v for the first product
   WgradSink init{EPI_WGRAD_INIT, nullptr, nullptr, nullptr, v, p, 0.f, K > 0};
-  upper_grad_seq(h, os, w, init, nullptr);
-  if (K > 0 || !l2) prepare_lower(h, os, w, lambda);
+  upper_grad_seq(h, os, w, lambda, K > 0 || !l2, init, nullptr);
   for (int k = 0; k < K; ++k) {
-    // v <- v - alpha (H v), p <- p + v fused into the weight-gradient epilogues of the product
-    WgradSink step{EPI_WGRAD_NEUMANN, nullptr, l2 ? lambda : nullptr, nullptr, v, p, alpha, k + 1 < K};
-    hvp_cached(h, os, v, step);
+    // v <- v - alpha (H v), p <- p + v fused into the weight-gradient epilogues of the product;
+    // for L2 decay the last step also applies the mixed VJP, so only d(lambda) is written
+    const bool last = k + 1 == K;
+    if (last && l2) {
+      WgradSink fin{EPI_WGRAD_NEUMANN_L2, dlambda, lambda, w, v, p, alpha, false};
+      hvp_cached(h, os, v, fin);
+    } else {
+      WgradSink step{EPI_WGRAD_NEUMANN, nullptr, l2 ? lambda : nullptr, nullptr, v, p, alpha, !last};
+      hvp_cached(h, os, v, step);
+    }
   }
-  if (l2) launch_mixed_l2(h->ctx, lambda, w, p, alpha, dlambda, h->d);
-  else mixed_reweight_seq(h, os, lambda, p, alpha, dlambda);
+  if (l2) {
+    if (K == 0) launch_mixed_l2(h->ctx, lambda, w, p, alpha, dlambda, h->d);
+  } else {
+    mixed_reweight_seq(h, os, lambda, p, alpha, dlambda);
+  }
   return finish(h);
 }
 
@@ -707,7 +759,7 @@ betty_status betty_hypergrad_fd(betty_handle h, const float* w, const float* lam
   float* nrm2 = h->f(h->scalars); float* eps = h->f(h->scalars) + 1;
   make_weight_operands(h, os, w);
   WgradSink init{EPI_WGRAD_INIT, nullptr, nullptr, nullptr, v, p, 0.f, false};
-  upper_grad_seq(h, os, w, init, nullptr);
+  upper_grad_seq(h, os, w, nullptr, false, init, nullptr);
   for (int k = 0; k < K; ++k) {
     launch_sumsq(h->ctx, v, h->d, h->at<double>(h->partials), nrm2);
     launch_fd_eps(h->ctx, nrm2, eps_scale, 1.f, eps);

@@ -86,140 +86,143 @@ template <> __device__ __forceinline__ void store4<__bf16>(__bf16* p, const floa
 }
 
 // One 32x32 MFMA block as seen by one lane: 16 accumulators = rows rb + 8*(k/4) + k%4 (k = 0..15)
-// of column col, with rb = block row + 4*(lane/32).  M, N = valid extent.  Every mode first issues
-// all of its loads for the 16 elements, then computes, then stores, so that the memory latency is
-// paid once per block and not once per element.
-template <typename T, int MODE>
-__device__ __forceinline__ void epilogue_block(const Epilogue& e, int M, int N, int rb, int col,
-                                               const f32x16 acc) {
+// of column col, with rb = block row + 4*(lane/32).  M, N = valid extent.
+//
+// The epilogue is split in two so that its memory latency hides behind the k loop: epi_prefetch
+// (before the loop) issues every load the mode needs for the block's 16 elements into EpiRegs;
+// epi_finish (after the loop) computes and stores.  Nothing the prefetch reads is written by the
+// same launch before epi_finish of the same element.
+struct EpiRegs { float a[16], b[16], c[16], d[16]; float colv; };
+
+__device__ __forceinline__ int epi_offset(int rb, int k, long long ld, int col) {
+  return (int)((long long)(rb + 8 * (k >> 2) + (k & 3)) * ld + col);   // layer slices are < 2^31 elements
+}
+
+template <int MODE>
+__device__ __forceinline__ void epi_prefetch(const Epilogue& e, int M, int N, int rb, int col, EpiRegs& R) {
   if (col >= N || rb >= M) return;
-  bool ok[16];
-  long long of[16];      // offset into the fp32 side arrays (ldf) or the flat slice (ldc)
   const long long ldx = MODE >= EPI_WGRAD ? e.ldc : e.ldf;
+  if constexpr (MODE == EPI_FWD || MODE == EPI_FWD_LAST || MODE == EPI_RFWD || MODE == EPI_RFWD_LAST)
+    R.colv = e.colvec ? e.colvec[col] : 0.f;
 #pragma unroll
   for (int k = 0; k < 16; ++k) {
-    const int row = rb + 8 * (k >> 2) + (k & 3);
-    ok[k] = row < M;
-    of[k] = (long long)row * ldx + col;
+    const bool ok = rb + 8 * (k >> 2) + (k & 3) < M;
+    const int o = epi_offset(rb, k, ldx, col);
+    if constexpr (MODE == EPI_BWD) {
+      R.a[k] = ok ? e.dphi[o] : 0.f;
+      R.b[k] = (ok && e.e_io) ? e.e_io[o] : 0.f;
+    } else if constexpr (MODE == EPI_RFWD) {
+      R.a[k] = ok ? e.dphi[o] : 0.f;
+    } else if constexpr (MODE == EPI_RBWD) {
+      R.a[k] = ok ? e.dphi[o] : 0.f;
+      R.b[k] = (ok && e.e) ? e.e[o] : 0.f;
+      R.c[k] = (ok && e.e) ? e.Rz[o] : 0.f;
+    } else if constexpr (MODE == EPI_WGRAD) {
+      R.a[k] = (ok && e.lam) ? e.lam[o] : 0.f;
+      R.b[k] = (ok && e.lam) ? e.x[o] : 0.f;
+    } else if constexpr (MODE == EPI_WGRAD_NEUMANN) {
+      R.a[k] = ok ? e.v[o] : 0.f;
+      R.b[k] = ok ? e.p[o] : 0.f;
+      R.c[k] = (ok && e.lam) ? e.lam[o] : 0.f;
+    } else if constexpr (MODE == EPI_WGRAD_NEUMANN_L2) {
+      R.a[k] = ok ? e.v[o] : 0.f;
+      R.b[k] = ok ? e.p[o] : 0.f;
+      R.c[k] = ok ? e.lam[o] : 0.f;
+      R.d[k] = ok ? e.x[o] : 0.f;
+    }
+  }
+}
+
+template <typename T, int MODE>
+__device__ __forceinline__ void epi_finish(const Epilogue& e, int M, int N, int rb, int col,
+                                           const f32x16 acc, const EpiRegs& R) {
+  if (col >= N || rb >= M) return;
+  const long long ldx = MODE >= EPI_WGRAD ? e.ldc : e.ldf;
+  bool ok[16];
+  int of[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    ok[k] = rb + 8 * (k >> 2) + (k & 3) < M;
+    of[k] = epi_offset(rb, k, ldx, col);
   }
   float val[16];
-  switch (MODE) {
-    case EPI_FWD: {
-      const float b = e.colvec ? e.colvec[col] : 0.f;
-      float d1[16], d2[16];
+  if constexpr (MODE == EPI_FWD) {
+    float d1[16], d2[16];
 #pragma unroll
-      for (int k = 0; k < 16; ++k) act_eval(e.act, acc[k] + b, val[k], d1[k], d2[k]);
-#pragma unroll
-      for (int k = 0; k < 16; ++k)
-        if (ok[k]) e.dphi_out[of[k]] = d1[k];
-      if (e.d2_out) {
-#pragma unroll
-        for (int k = 0; k < 16; ++k)
-          if (ok[k]) e.d2_out[of[k]] = d2[k];
-      }
-      break;
-    }
-    case EPI_FWD_LAST:
-    case EPI_RFWD_LAST: {
-      const float b = e.colvec ? e.colvec[col] : 0.f;
-#pragma unroll
-      for (int k = 0; k < 16; ++k)
-        if (ok[k]) e.f0[of[k]] = acc[k] + b;
-      return;
-    }
-    case EPI_BWD: {
-      float dp[16], ee[16];
-#pragma unroll
-      for (int k = 0; k < 16; ++k) dp[k] = ok[k] ? e.dphi[of[k]] : 0.f;
-      if (e.e_io) {
-#pragma unroll
-        for (int k = 0; k < 16; ++k) ee[k] = ok[k] ? e.e_io[of[k]] : 0.f;
-#pragma unroll
-        for (int k = 0; k < 16; ++k)
-          if (ok[k]) e.e_io[of[k]] = acc[k] * ee[k];
-      }
-#pragma unroll
-      for (int k = 0; k < 16; ++k) val[k] = acc[k] * dp[k];
-      break;
-    }
-    case EPI_RFWD: {
-      const float b = e.colvec ? e.colvec[col] : 0.f;
-      float dp[16];
-#pragma unroll
-      for (int k = 0; k < 16; ++k) dp[k] = ok[k] ? e.dphi[of[k]] : 0.f;
-#pragma unroll
-      for (int k = 0; k < 16; ++k)
-        if (ok[k]) e.f0[of[k]] = acc[k] + b;
-#pragma unroll
-      for (int k = 0; k < 16; ++k) val[k] = dp[k] * (acc[k] + b);
-      break;
-    }
-    case EPI_RBWD: {
-      float dp[16], ee[16], rz[16];
-#pragma unroll
-      for (int k = 0; k < 16; ++k) dp[k] = ok[k] ? e.dphi[of[k]] : 0.f;
-      if (e.e) {
-#pragma unroll
-        for (int k = 0; k < 16; ++k) { ee[k] = ok[k] ? e.e[of[k]] : 0.f; rz[k] = ok[k] ? e.Rz[of[k]] : 0.f; }
-      } else {
-#pragma unroll
-        for (int k = 0; k < 16; ++k) { ee[k] = 0.f; rz[k] = 0.f; }
-      }
-#pragma unroll
-      for (int k = 0; k < 16; ++k) val[k] = acc[k] * dp[k] + ee[k] * rz[k];
-      break;
-    }
-    case EPI_WGRAD: {             // C = acc (+ 2 e^lam x)
-      float lm[16], xx[16];
-      if (e.lam) {
-#pragma unroll
-        for (int k = 0; k < 16; ++k) { lm[k] = ok[k] ? e.lam[of[k]] : 0.f; xx[k] = ok[k] ? e.x[of[k]] : 0.f; }
-#pragma unroll
-        for (int k = 0; k < 16; ++k)
-          if (ok[k]) e.C[of[k]] = acc[k] + 2.f * expf(lm[k]) * xx[k];
-      } else {
-#pragma unroll
-        for (int k = 0; k < 16; ++k)
-          if (ok[k]) e.C[of[k]] = acc[k];
-      }
-      return;
-    }
-    case EPI_WGRAD_INIT: {        // v = p = acc ; operand copies of v
-#pragma unroll
-      for (int k = 0; k < 16; ++k) {
-        val[k] = ok[k] ? acc[k] : 0.f;
-        if (ok[k]) { e.v[of[k]] = acc[k]; e.p[of[k]] = acc[k]; }
-      }
-      break;
-    }
-    case EPI_WGRAD_NEUMANN: {     // Hv = acc (+ 2 e^lam v); v <- v - alpha Hv; p <- p + v; copies of v
-      float vo[16], po[16], lm[16];
-#pragma unroll
-      for (int k = 0; k < 16; ++k) { vo[k] = ok[k] ? e.v[of[k]] : 0.f; po[k] = ok[k] ? e.p[of[k]] : 0.f; }
-      if (e.lam) {
-#pragma unroll
-        for (int k = 0; k < 16; ++k) lm[k] = ok[k] ? e.lam[of[k]] : 0.f;
-      }
-#pragma unroll
-      for (int k = 0; k < 16; ++k) {
-        float hv = acc[k];
-        if (e.lam) hv += 2.f * expf(lm[k]) * vo[k];
-        val[k] = ok[k] ? vo[k] - e.alpha * hv : 0.f;
-      }
-#pragma unroll
-      for (int k = 0; k < 16; ++k)
-        if (ok[k]) { e.v[of[k]] = val[k]; e.p[of[k]] = po[k] + val[k]; }
-      break;
-    }
-    default:
-      return;
-  }
-  // operand-typed copies: row-major element by element, transposed as 4-element vectors
-  if (MODE != EPI_WGRAD_INIT && MODE != EPI_WGRAD_NEUMANN) {
+    for (int k = 0; k < 16; ++k) act_eval(e.act, acc[k] + R.colv, val[k], d1[k], d2[k]);
 #pragma unroll
     for (int k = 0; k < 16; ++k)
-      if (!ok[k]) val[k] = 0.f;
+      if (ok[k]) e.dphi_out[of[k]] = d1[k];
+    if (e.d2_out) {
+#pragma unroll
+      for (int k = 0; k < 16; ++k)
+        if (ok[k]) e.d2_out[of[k]] = d2[k];
+    }
+  } else if constexpr (MODE == EPI_FWD_LAST || MODE == EPI_RFWD_LAST) {
+#pragma unroll
+    for (int k = 0; k < 16; ++k)
+      if (ok[k]) e.f0[of[k]] = acc[k] + R.colv;
+    return;
+  } else if constexpr (MODE == EPI_BWD) {
+    if (e.e_io) {
+#pragma unroll
+      for (int k = 0; k < 16; ++k)
+        if (ok[k]) e.e_io[of[k]] = acc[k] * R.b[k];
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) val[k] = acc[k] * R.a[k];
+  } else if constexpr (MODE == EPI_RFWD) {
+#pragma unroll
+    for (int k = 0; k < 16; ++k)
+      if (ok[k]) e.f0[of[k]] = acc[k] + R.colv;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) val[k] = R.a[k] * (acc[k] + R.colv);
+  } else if constexpr (MODE == EPI_RBWD) {
+#pragma unroll
+    for (int k = 0; k < 16; ++k) val[k] = acc[k] * R.a[k] + R.b[k] * R.c[k];
+  } else if constexpr (MODE == EPI_WGRAD) {            // C = acc (+ 2 e^lam x)
+    if (e.lam) {
+#pragma unroll
+      for (int k = 0; k < 16; ++k)
+        if (ok[k]) e.C[of[k]] = acc[k] + 2.f * expf(R.a[k]) * R.b[k];
+    } else {
+#pragma unroll
+      for (int k = 0; k < 16; ++k)
+        if (ok[k]) e.C[of[k]] = acc[k];
+    }
+    return;
+  } else if constexpr (MODE == EPI_WGRAD_INIT) {       // v = p = acc ; operand copies of v
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      val[k] = acc[k];
+      if (ok[k]) { e.v[of[k]] = acc[k]; e.p[of[k]] = acc[k]; }
+    }
+  } else if constexpr (MODE == EPI_WGRAD_NEUMANN) {    // Hv = acc (+ 2 e^lam v); v -= alpha Hv; p += v
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      float hv = acc[k];
+      if (e.lam) hv += 2.f * expf(R.c[k]) * R.a[k];
+      val[k] = R.a[k] - e.alpha * hv;
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k)
+      if (ok[k]) { e.v[of[k]] = val[k]; e.p[of[k]] = R.b[k] + val[k]; }
+  } else if constexpr (MODE == EPI_WGRAD_NEUMANN_L2) {  // final step: only d(lambda) leaves the kernel
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const float el = 2.f * expf(R.c[k]);
+      const float vn = R.a[k] - e.alpha * (acc[k] + el * R.a[k]);
+      if (ok[k]) e.C[of[k]] = -el * R.d[k] * (e.alpha * (R.b[k] + vn));
+    }
+    return;
+  } else {
+    return;
   }
+  // operand-typed copies: row-major element by element, transposed as 4-element vectors; rows
+  // beyond M are written as zeros (they are padding of the transposed operand)
+#pragma unroll
+  for (int k = 0; k < 16; ++k)
+    if (!ok[k]) val[k] = 0.f;
   if (e.out) {
     T* o = (T*)e.out;
 #pragma unroll
@@ -275,6 +278,12 @@ __device__ void bias_rows(const BiasJob& j, int row) {
       j.p[row] += vn;
       break;
     }
+    case EPI_WGRAD_NEUMANN_L2: {
+      const float vo = j.v[row], el = 2.f * expf(j.lam[row]);
+      const float vn = vo - j.alpha * (acc + el * vo);
+      j.C[row] = -el * j.x[row] * (j.alpha * (j.p[row] + vn));
+      break;
+    }
     default: break;
   }
 }
@@ -328,6 +337,21 @@ __global__ __launch_bounds__(64 * WPG * KG) void gemm_fused_kernel(GemmBatch bat
   for (int i = 0; i < TM * TN; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+  // epilogue inputs of this wavefront's blocks: requested now, consumed after the k loop.  Only
+  // group 0 finishes the tile.  (With several blocks per wavefront the prefetch is kept for the
+  // parameter-shaped modes, whose epilogue moves far more bytes than their k loop.)
+  constexpr bool PREFETCH = TM * TN == 1 || MODE >= EPI_WGRAD;
+  const Epilogue& e = batch.p[pi].e;
+  EpiRegs pre[TM * TN];
+  if constexpr (PREFETCH) {
+    if (kg == 0) {
+#pragma unroll
+      for (int ij = 0; ij < TM * TN; ++ij)
+        epi_prefetch<MODE>(e, g.M, g.N, m0 + wm * TM * 32 + (ij / TN) * 32 + 4 * (lane >> 5),
+                           n0 + wn * TN * 32 + (ij % TN) * 32 + (lane & 31), pre[ij]);
+    }
+  }
 
   // Two register sets hold the global loads of the next two k-tiles, so two tiles' worth of
   // loads are in flight while a third is multiplied out of LDS.
@@ -413,11 +437,13 @@ __global__ __launch_bounds__(64 * WPG * KG) void gemm_fused_kernel(GemmBatch bat
   }
 
   // ---- epilogue from registers, one MFMA block at a time
-  const Epilogue& e = batch.p[pi].e;
 #pragma unroll
-  for (int ij = 0; ij < TM * TN; ++ij)
-    epilogue_block<T, MODE>(e, g.M, g.N, m0 + wm * TM * 32 + (ij / TN) * 32 + 4 * (lane >> 5),
-                            n0 + wn * TN * 32 + (ij % TN) * 32 + (lane & 31), acc[ij]);
+  for (int ij = 0; ij < TM * TN; ++ij) {
+    const int rb = m0 + wm * TM * 32 + (ij / TN) * 32 + 4 * (lane >> 5);
+    const int col = n0 + wn * TN * 32 + (ij % TN) * 32 + (lane & 31);
+    if constexpr (!PREFETCH) epi_prefetch<MODE>(e, g.M, g.N, rb, col, pre[ij]);
+    epi_finish<T, MODE>(e, g.M, g.N, rb, col, acc[ij], pre[ij]);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -461,6 +487,7 @@ static void launch_wgrad_mode(int mode, int total, hipStream_t st, const GemmBat
   switch (mode) {
 #define BETTY_CASE_W(M_) case M_: launch_one<T, BT, 4, 1, M_>(total, st, b, err); break;
     BETTY_CASE_W(EPI_WGRAD) BETTY_CASE_W(EPI_WGRAD_INIT) BETTY_CASE_W(EPI_WGRAD_NEUMANN)
+    BETTY_CASE_W(EPI_WGRAD_NEUMANN_L2)
 #undef BETTY_CASE_W
     default: err = hipErrorInvalidValue; break;
   }

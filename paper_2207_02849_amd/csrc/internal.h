@@ -42,7 +42,8 @@ enum EpiMode {
   EPI_RBWD,              // out = acc * dphi + e * Rz
   EPI_WGRAD,             // C = acc (+ 2 exp(lam) x)                       flat parameter layout
   EPI_WGRAD_INIT,        // v = p = acc; out = operand copies of v
-  EPI_WGRAD_NEUMANN      // Hv = acc (+ 2 exp(lam) v); v -= alpha Hv; p += v; out = copies of v
+  EPI_WGRAD_NEUMANN,     // Hv = acc (+ 2 exp(lam) v); v -= alpha Hv; p += v; out = copies of v
+  EPI_WGRAD_NEUMANN_L2   // last step for L2 decay: same update in registers, C = -2 exp(lam) x (alpha p)
 };
 
 struct Epilogue {
@@ -130,7 +131,8 @@ struct LossArgs {
   float* P;                             // softmax probabilities [rows][ldz] (CE)
   void* D; int ldD; void* Dt; int ldDt;  // s_i * dl_i/dz as GEMM operands, both orientations
 };
-void launch_loss_rows(Ctx&, Elem, const LossArgs&);
+struct LossBatch { int n = 0; LossArgs a[2]; };     // up to two batches (train, validation) per launch
+void launch_loss_rows(Ctx&, Elem, const LossBatch&);
 // Rdelta_L (fp32) = s_i * (d^2 l_i/dz^2) Rz_i
 void launch_loss_hessian_rows(Ctx&, Elem, int loss, const float* P, const float* Rz, long long ld,
                               const float* s, int rows, int C, void* D, int ldD, void* Dt, int ldDt);

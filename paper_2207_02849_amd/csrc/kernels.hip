@@ -105,8 +105,11 @@ void launch_convert_dual(Ctx& ctx, Elem elem, const float* src, long long lds, f
 // ------------------------------------------------------------------------------------------
 
 template <typename T>
-__global__ __launch_bounds__(256) void loss_rows_kernel(LossArgs a) {
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+__global__ __launch_bounds__(256) void loss_rows_kernel(LossBatch lb) {
+  const int blocks0 = (lb.a[0].rows + 3) / 4;
+  const int which = (lb.n > 1 && (int)blockIdx.x >= blocks0) ? 1 : 0;
+  const LossArgs& a = lb.a[which];
+  const int row = ((int)blockIdx.x - (which ? blocks0 : 0)) * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (row >= a.rows) return;
   const float* z = a.Z + (long long)row * a.ldz;
   float ell, m = 0.f, sum = 1.f;
@@ -160,11 +163,13 @@ __global__ __launch_bounds__(256) void loss_rows_kernel(LossArgs a) {
   }
 }
 
-void launch_loss_rows(Ctx& ctx, Elem elem, const LossArgs& a) {
-  if (a.rows <= 0) return;
+void launch_loss_rows(Ctx& ctx, Elem elem, const LossBatch& lb) {
+  int blocks = 0;
+  for (int i = 0; i < lb.n; ++i) blocks += (lb.a[i].rows + 3) / 4;
+  if (blocks <= 0) return;
   Launch l(ctx, BETTY_K_LOSS);
-  if (elem == ELEM_BF16) loss_rows_kernel<__bf16><<<(a.rows + 3) / 4, 256, 0, ctx.stream>>>(a);
-  else loss_rows_kernel<float><<<(a.rows + 3) / 4, 256, 0, ctx.stream>>>(a);
+  if (elem == ELEM_BF16) loss_rows_kernel<__bf16><<<blocks, 256, 0, ctx.stream>>>(lb);
+  else loss_rows_kernel<float><<<blocks, 256, 0, ctx.stream>>>(lb);
 }
 
 template <typename T>
