@@ -163,7 +163,9 @@ typedef struct {
 
 enum {
   BETTY_K_GEMM = 0, BETTY_K_EPILOGUE = 1, BETTY_K_LOSS = 2, BETTY_K_SHADOW = 3,
-  BETTY_K_VECTOR = 4, BETTY_K_REDUCE = 5, BETTY_K_WNET = 6, BETTY_K_OTHER = 7
+  BETTY_K_VECTOR = 4, BETTY_K_REDUCE = 5, BETTY_K_WNET = 6, BETTY_K_OTHER = 7,
+  BETTY_K_GEMM_UPDATE = 8   /* weight-gradient GEMM whose epilogue applies the Neumann update:
+                               flops = its 2MNK, bytes = 20 per parameter (v, p, lambda read; v, p written) */
 };
 
 /* While enabled, every kernel launch of the handle is bracketed by HIP events on the

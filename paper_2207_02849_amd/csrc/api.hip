@@ -75,6 +75,16 @@ struct betty_handle_s {
   OperandSet sets[2];        // [0]: element type of desc.prec; [1]: fp32 set for finite differences when prec is bf16
   size_t vec_g = 0, vec_v = 0, vec_p = 0, vec_Hv = 0, vec_wpm = 0, vec_Gm = 0;
   size_t partials = 0, scalars = 0;
+  // a hypergradient call repeated with the same arguments is replayed from a captured HIP graph
+  struct GraphSlot {
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    const void* w = nullptr; const void* lam = nullptr; void* out = nullptr;
+    int K = -1; float alpha = 0.f, eps = 0.f;
+    int seen = 0;
+  };
+  GraphSlot graph_neumann, graph_fd;
+  bool use_graphs = true;
   int tune_target_blocks = 256, tune_tile128_min = 192;   // see plan_chain
   int tune_wgrad_cfg = GEMM_64x1;
 
@@ -407,7 +417,12 @@ void wgrad_batch(betty_handle h, OperandSet& os, int side, bool rop, const Wgrad
         j.alpha = k.alpha;
       }
     }
-    launch_gemm_batch(h->ctx, os.elem, h->tune_wgrad_cfg, b, flops);
+    double params = 0;
+    for (int i = 0; i < b.n; ++i) {
+      const LayerInfo& li = h->layers[l0 + i - 1];
+      params += (double)li.n_in * li.n_out + (h->desc.has_bias ? li.n_out : 0);
+    }
+    launch_gemm_batch(h->ctx, os.elem, h->tune_wgrad_cfg, b, flops, 20.0 * params);
   }
 }
 
@@ -555,6 +570,68 @@ betty_status finish(betty_handle h) {
 
 }  // namespace
 
+static void drop_graph(betty_handle_s::GraphSlot& g) {
+  if (g.exec) (void)hipGraphExecDestroy(g.exec);
+  if (g.graph) (void)hipGraphDestroy(g.graph);
+  g = betty_handle_s::GraphSlot();
+}
+
+static void drop_graphs(betty_handle h) { drop_graph(h->graph_neumann); drop_graph(h->graph_fd); }
+
+// Runs `body` (which only enqueues kernels on the bound stream) directly the first time a given
+// argument set is seen, captures it into a graph the second time, and replays the graph from then
+// on.  Any capture failure switches graphs off for the handle and runs the body directly.
+template <typename Body>
+static betty_status run_cached(betty_handle h, betty_handle_s::GraphSlot& g, const void* w, const void* lam,
+                               void* out, int K, float alpha, float eps, Body body) {
+  const bool eligible = h->use_graphs && !h->ctx.profiling && h->ctx.stream != nullptr;
+  if (!eligible) { body(); return finish(h); }
+  const bool same = g.seen > 0 && g.w == w && g.lam == lam && g.out == out && g.K == K && g.alpha == alpha && g.eps == eps;
+  if (same && g.exec) {
+    if (hipGraphLaunch(g.exec, h->ctx.stream) != hipSuccess) return fail(h, BETTY_EDEVICE, "hipGraphLaunch failed");
+    return BETTY_OK;
+  }
+  if (!same) {
+    drop_graph(g);
+    g.w = w; g.lam = lam; g.out = out; g.K = K; g.alpha = alpha; g.eps = eps; g.seen = 1;
+    body();
+    return finish(h);
+  }
+  if (hipStreamBeginCapture(h->ctx.stream, hipStreamCaptureModeThreadLocal) != hipSuccess) {
+    (void)hipGetLastError();
+    h->use_graphs = false;
+    body();
+    return finish(h);
+  }
+  body();
+  hipGraph_t graph = nullptr;
+  const hipError_t e_end = hipStreamEndCapture(h->ctx.stream, &graph);
+  hipGraphExec_t exec = nullptr;
+  if (e_end != hipSuccess || h->ctx.first_error != hipSuccess || !graph ||
+      hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) != hipSuccess) {
+    (void)hipGetLastError();
+    if (graph) (void)hipGraphDestroy(graph);
+    h->ctx.first_error = hipSuccess;
+    h->use_graphs = false;
+    body();                     // nothing ran during the failed capture
+    return finish(h);
+  }
+  g.graph = graph; g.exec = exec;
+  if (hipGraphLaunch(g.exec, h->ctx.stream) != hipSuccess) return fail(h, BETTY_EDEVICE, "hipGraphLaunch failed");
+  return BETTY_OK;
+}
+
+static betty_status check_hyper_args(betty_handle h, const float* w, const float* lambda, int K, float alpha,
+                                     float* dlambda) {
+  CHECK(check_ready(h));
+  CHECK(check_vec(h, w, "w")); CHECK(check_vec(h, lambda, "lambda")); CHECK(check_vec(h, dlambda, "dlambda"));
+  if (K < 0) return fail(h, BETTY_EINVAL, "K must be >= 0 (got %d)", K);
+  if (!std::isfinite(alpha)) return fail(h, BETTY_EINVAL, "alpha must be finite");
+  if (overlaps(dlambda, h->n_hyper * 4, w, h->d * 4) || overlaps(dlambda, h->n_hyper * 4, lambda, h->n_hyper * 4))
+    return fail(h, BETTY_EINVAL, "dlambda overlaps an input");
+  return BETTY_OK;
+}
+
 extern "C" {
 
 betty_status betty_create(const betty_problem_desc* desc, betty_handle* out) {
@@ -599,6 +676,7 @@ betty_status betty_create(const betty_problem_desc* desc, betty_handle* out) {
 
 void betty_destroy(betty_handle h) {
   if (!h) return;
+  drop_graphs(h);
   for (auto& r : h->ctx.recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
   delete h;
 }
@@ -615,6 +693,7 @@ betty_status betty_bind(betty_handle h, void* workspace, size_t bytes, void* hip
   if (bytes < h->ws_need) return fail(h, BETTY_EWORKSPACE, "workspace has %zu bytes, %zu needed", bytes, h->ws_need);
   h->ws = (char*)workspace;
   h->ctx.stream = (hipStream_t)hip_stream;
+  drop_graphs(h);
   h->bound = true;
   h->batches = false;
   launch_fill_zero(h->ctx, h->ws, h->ws_need);
@@ -630,6 +709,7 @@ betty_status betty_set_batches(betty_handle h, betty_batch train, betty_batch va
     if (h->desc.loss == BETTY_LOSS_SOFTMAX_CE) CHECK(check_vec(h, b[s].y, s ? "val.y" : "train.y"));
     else CHECK(check_vec(h, b[s].target, s ? "val.target" : "train.target"));
   }
+  drop_graphs(h);
   h->batch[0] = train;
   h->batch[1] = val;
   const LayerInfo& l0 = h->layers[0];
@@ -706,45 +786,36 @@ betty_status betty_mixed_vjp(betty_handle h, const float* w, const float* lambda
   return finish(h);
 }
 
-static betty_status check_hyper_args(betty_handle h, const float* w, const float* lambda, int K, float alpha,
-                                     float* dlambda) {
-  CHECK(check_ready(h));
-  CHECK(check_vec(h, w, "w")); CHECK(check_vec(h, lambda, "lambda")); CHECK(check_vec(h, dlambda, "dlambda"));
-  if (K < 0) return fail(h, BETTY_EINVAL, "K must be >= 0 (got %d)", K);
-  if (!std::isfinite(alpha)) return fail(h, BETTY_EINVAL, "alpha must be finite");
-  if (overlaps(dlambda, h->n_hyper * 4, w, h->d * 4) || overlaps(dlambda, h->n_hyper * 4, lambda, h->n_hyper * 4))
-    return fail(h, BETTY_EINVAL, "dlambda overlaps an input");
-  return BETTY_OK;
-}
-
 betty_status betty_hypergrad_neumann(betty_handle h, const float* w, const float* lambda, int K, float alpha,
                                      float* dlambda) {
   CHECK(check_hyper_args(h, w, lambda, K, alpha, dlambda));
-  OperandSet& os = h->sets[0];
-  const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
-  float* v = h->f(h->vec_v); float* p = h->f(h->vec_p);
-  make_weight_operands(h, os, w);
-  // g = grad_w L_U lands directly in v and p, with the operand copies of v for the first product
-  WgradSink init{EPI_WGRAD_INIT, nullptr, nullptr, nullptr, v, p, 0.f, K > 0};
-  upper_grad_seq(h, os, w, lambda, K > 0 || !l2, init, nullptr);
-  for (int k = 0; k < K; ++k) {
-    // v <- v - alpha (H v), p <- p + v fused into the weight-gradient epilogues of the product;
-    // for L2 decay the last step also applies the mixed VJP, so only d(lambda) is written
-    const bool last = k + 1 == K;
-    if (last && l2) {
-      WgradSink fin{EPI_WGRAD_NEUMANN_L2, dlambda, lambda, w, v, p, alpha, false};
-      hvp_cached(h, os, v, fin);
-    } else {
-      WgradSink step{EPI_WGRAD_NEUMANN, nullptr, l2 ? lambda : nullptr, nullptr, v, p, alpha, !last};
-      hvp_cached(h, os, v, step);
+  auto body = [=]() {
+    OperandSet& os = h->sets[0];
+    const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
+    float* v = h->f(h->vec_v); float* p = h->f(h->vec_p);
+    make_weight_operands(h, os, w);
+    // g = grad_w L_U lands directly in v and p, with the operand copies of v for the first product
+    WgradSink init{EPI_WGRAD_INIT, nullptr, nullptr, nullptr, v, p, 0.f, K > 0};
+    upper_grad_seq(h, os, w, lambda, K > 0 || !l2, init, nullptr);
+    for (int k = 0; k < K; ++k) {
+      // v <- v - alpha (H v), p <- p + v fused into the weight-gradient epilogues of the product;
+      // for L2 decay the last step also applies the mixed VJP, so only d(lambda) is written
+      const bool last = k + 1 == K;
+      if (last && l2) {
+        WgradSink fin{EPI_WGRAD_NEUMANN_L2, dlambda, lambda, w, v, p, alpha, false};
+        hvp_cached(h, os, v, fin);
+      } else {
+        WgradSink step{EPI_WGRAD_NEUMANN, nullptr, l2 ? lambda : nullptr, nullptr, v, p, alpha, !last};
+        hvp_cached(h, os, v, step);
+      }
     }
-  }
-  if (l2) {
-    if (K == 0) launch_mixed_l2(h->ctx, lambda, w, p, alpha, dlambda, h->d);
-  } else {
-    mixed_reweight_seq(h, os, lambda, p, alpha, dlambda);
-  }
-  return finish(h);
+    if (l2) {
+      if (K == 0) launch_mixed_l2(h->ctx, lambda, w, p, alpha, dlambda, h->d);
+    } else {
+      mixed_reweight_seq(h, os, lambda, p, alpha, dlambda);
+    }
+  };
+  return run_cached(h, h->graph_neumann, w, lambda, dlambda, K, alpha, 0.f, body);
 }
 
 betty_status betty_hypergrad_fd(betty_handle h, const float* w, const float* lambda, int K, float alpha,
@@ -753,28 +824,30 @@ betty_status betty_hypergrad_fd(betty_handle h, const float* w, const float* lam
   if (!std::isfinite(eps_scale) || eps_scale <= 0.f) return fail(h, BETTY_EINVAL, "eps_scale must be positive and finite");
   if (h->desc.hp != BETTY_HP_L2_DECAY)
     return fail(h, BETTY_EUNSUPPORTED, "finite-difference variant is implemented for L2-decay hyperparameters only");
-  OperandSet& os = fd_operands(h);
-  float* v = h->f(h->vec_v); float* p = h->f(h->vec_p); float* Gp = h->f(h->vec_Hv);
-  float* Gm = h->f(h->vec_Gm); float* wpm = h->f(h->vec_wpm);
-  float* nrm2 = h->f(h->scalars); float* eps = h->f(h->scalars) + 1;
-  make_weight_operands(h, os, w);
-  WgradSink init{EPI_WGRAD_INIT, nullptr, nullptr, nullptr, v, p, 0.f, false};
-  upper_grad_seq(h, os, w, nullptr, false, init, nullptr);
-  for (int k = 0; k < K; ++k) {
-    launch_sumsq(h->ctx, v, h->d, h->at<double>(h->partials), nrm2);
-    launch_fd_eps(h->ctx, nrm2, eps_scale, 1.f, eps);
-    launch_fd_perturb(h->ctx, w, v, eps, +1.f, wpm, h->d);
-    make_weight_operands(h, os, wpm);
-    lower_grad_seq(h, os, wpm, lambda, Gp, nullptr);
-    launch_fd_perturb(h->ctx, w, v, eps, -1.f, wpm, h->d);
-    make_weight_operands(h, os, wpm);
-    lower_grad_seq(h, os, wpm, lambda, Gm, nullptr);
-    launch_fd_update(h->ctx, v, p, Gp, Gm, eps, alpha, h->d);
-  }
-  launch_sumsq(h->ctx, p, h->d, h->at<double>(h->partials), nrm2);
-  launch_fd_eps(h->ctx, nrm2, eps_scale, alpha, eps);
-  launch_mixed_l2_fd(h->ctx, lambda, w, p, alpha, eps, dlambda, h->d);
-  return finish(h);
+  auto body = [=]() {
+    OperandSet& os = fd_operands(h);
+    float* v = h->f(h->vec_v); float* p = h->f(h->vec_p); float* Gp = h->f(h->vec_Hv);
+    float* Gm = h->f(h->vec_Gm); float* wpm = h->f(h->vec_wpm);
+    float* nrm2 = h->f(h->scalars); float* eps = h->f(h->scalars) + 1;
+    make_weight_operands(h, os, w);
+    WgradSink init{EPI_WGRAD_INIT, nullptr, nullptr, nullptr, v, p, 0.f, false};
+    upper_grad_seq(h, os, w, nullptr, false, init, nullptr);
+    for (int k = 0; k < K; ++k) {
+      launch_sumsq(h->ctx, v, h->d, h->at<double>(h->partials), nrm2);
+      launch_fd_eps(h->ctx, nrm2, eps_scale, 1.f, eps);
+      launch_fd_perturb(h->ctx, w, v, eps, +1.f, wpm, h->d);
+      make_weight_operands(h, os, wpm);
+      lower_grad_seq(h, os, wpm, lambda, Gp, nullptr);
+      launch_fd_perturb(h->ctx, w, v, eps, -1.f, wpm, h->d);
+      make_weight_operands(h, os, wpm);
+      lower_grad_seq(h, os, wpm, lambda, Gm, nullptr);
+      launch_fd_update(h->ctx, v, p, Gp, Gm, eps, alpha, h->d);
+    }
+    launch_sumsq(h->ctx, p, h->d, h->at<double>(h->partials), nrm2);
+    launch_fd_eps(h->ctx, nrm2, eps_scale, alpha, eps);
+    launch_mixed_l2_fd(h->ctx, lambda, w, p, alpha, eps, dlambda, h->d);
+  };
+  return run_cached(h, h->graph_fd, w, lambda, dlambda, K, alpha, eps_scale, body);
 }
 
 betty_status betty_apply_label_noise(betty_handle h, const int32_t* y, const uint32_t* words, const int32_t* alt,

@@ -516,7 +516,7 @@ int gemm_ktile_elems(Elem elem) { return GEMM_NCH * (elem == ELEM_BF16 ? 8 : 4);
 int gemm_cfg_tile(int cfg) { return (cfg == GEMM_128x1 || cfg == GEMM_128x2) ? 128 : cfg == GEMM_32x16 ? 32 : 64; }
 static int gemm_cfg_waves(int cfg) { return cfg == GEMM_128x2 ? 8 : cfg == GEMM_64x4 ? 16 : cfg == GEMM_32x16 ? 16 : 4; }
 
-void launch_gemm_batch(Ctx& ctx, Elem elem, int cfg, GemmBatch& b, double flops) {
+void launch_gemm_batch(Ctx& ctx, Elem elem, int cfg, GemmBatch& b, double flops, double bytes) {
   const int bt = gemm_cfg_tile(cfg);
   const int rows_per_block = gemm_cfg_waves(cfg);
   int blocks = 0;
@@ -534,7 +534,9 @@ void launch_gemm_batch(Ctx& ctx, Elem elem, int cfg, GemmBatch& b, double flops)
   b.bias_begin[b.n_bias] = bias_blocks;
   const int total = blocks + bias_blocks;
   if (total <= 0) return;
-  Launch l(ctx, BETTY_K_GEMM, flops, 0);
+  const int mode0 = b.p[0].e.mode;
+  const bool update = mode0 == EPI_WGRAD_NEUMANN || mode0 == EPI_WGRAD_NEUMANN_L2;
+  Launch l(ctx, update ? BETTY_K_GEMM_UPDATE : BETTY_K_GEMM, flops, bytes);
   hipError_t err = hipSuccess;
   if (elem == ELEM_BF16) launch_elem<__bf16>(cfg, b.p[0].e.mode, total, ctx.stream, b, err);
   else launch_elem<float>(cfg, b.p[0].e.mode, total, ctx.stream, b, err);

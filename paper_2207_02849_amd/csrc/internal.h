@@ -103,7 +103,8 @@ struct Launch {   // RAII bracket around one kernel launch
 // ---- gemm.hip
 int gemm_ktile_elems(Elem elem);
 int gemm_cfg_tile(int cfg);
-void launch_gemm_batch(Ctx& ctx, Elem elem, int cfg, GemmBatch& batch, double algorithmic_flops);
+void launch_gemm_batch(Ctx& ctx, Elem elem, int cfg, GemmBatch& batch, double algorithmic_flops,
+                       double algorithmic_bytes = 0);
 
 // ---- kernels.hip : operand conversion -----------------------------------------------------
 // out (row-major [rows_p][ld]) and outT ([cols_p][ldT]) = convert(scale * src[r * lds + c]); either may be null

@@ -214,3 +214,40 @@ def test_zero_direction_and_fd_zero_gradient():
     Hv = b.betty_hvp(w, lam, torch.zeros(wl.d, device="cuda"))
     torch.cuda.synchronize()
     assert not Hv.any()
+
+
+@pytest.mark.parametrize("kind", ["l2", "reweight"])
+def test_graph_replays_match_first_direct_run(kind):
+    """A hypergradient call repeated with identical arguments is captured into a HIP graph on its
+    second run and replayed afterwards: every replay, with other work and synchronisations in
+    between, must reproduce the first (directly launched) result bit for bit."""
+    wl = wk.tiny(kind=kind, act="gelu", dims=(300, 200, 150, 10), batch=130, prec="bf16", hidden=100)
+    b = binding.from_workload(wl)
+    w, lam = dev(wl.w), dev(wl.lam)
+    v = dev(np.random.default_rng(2).standard_normal(wl.d).astype(np.float32))
+    out = torch.empty(b.n_hyper, device="cuda")
+    out_fd = torch.empty(b.n_hyper, device="cuda")
+    b.betty_hypergrad_neumann(w, lam, 3, 0.05, out=out)          # direct
+    torch.cuda.synchronize()
+    first = out.clone()
+    first_fd = None
+    Hv0 = b.betty_hvp(w, lam, v).clone()
+    for rep in range(5):                                         # capture on rep 0, replay after
+        out.zero_()
+        b.betty_hypergrad_neumann(w, lam, 3, 0.05, out=out)
+        Hv = b.betty_hvp(w, lam, v)                              # direct work between replays
+        if kind == "l2":
+            out_fd.zero_()
+            b.betty_hypergrad_fd(w, lam, 2, 0.05, 0.01, out=out_fd)
+        torch.cuda.synchronize()
+        assert torch.equal(out, first), rep
+        assert torch.equal(Hv, Hv0), rep
+        if kind == "l2":
+            if first_fd is None:
+                first_fd = out_fd.clone()
+            assert torch.equal(out_fd, first_fd), rep
+    # different arguments drop the graph and still give the right answer
+    got = b.betty_hypergrad_neumann(w, lam, 2, 0.05)
+    ref = orc.hypergrad_neumann(oracle_problem(wl), wl.w, wl.lam, 2, 0.05)
+    assert rel_l2(host(got), ref) < 2e-2
+    b.close()
