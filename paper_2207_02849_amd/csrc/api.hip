@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <new>
 #include <cstring>
 
@@ -85,7 +86,7 @@ struct betty_handle_s {
   };
   GraphSlot graph_neumann, graph_fd;
   bool use_graphs = true;
-  int tune_target_blocks = 256, tune_tile128_min = 192;   // see plan_chain
+  int tune_target_blocks = 256, tune_tile128_min = 512;   // see plan_chain (measured on 512x4096x8192: 64-tiles beat 128-tiles until the grid is several waves deep)
   int tune_wgrad_cfg = GEMM_64x1;
 
   template <typename T = void> T* at(size_t off) const { return (T*)(ws + off); }
@@ -669,6 +670,13 @@ betty_status betty_create(const betty_problem_desc* desc, betty_handle* out) {
   h->d = off;
   h->n_hyper = desc->hp == BETTY_HP_L2_DECAY ? h->d : (size_t)3 * desc->wnet_hidden + 1;
   h->max_Bp = std::max(padup(desc->batch_train), padup(desc->batch_val));
+  // tuning overrides for experiments: BETTY_TUNE="wgrad=<cfg>,tile128=<n>,blocks=<n>" (see plan_chain)
+  if (const char* t = getenv("BETTY_TUNE")) {
+    int v;
+    if (const char* q = strstr(t, "wgrad=")) if (sscanf(q + 6, "%d", &v) == 1 && (v == GEMM_128x1 || v == GEMM_64x1)) h->tune_wgrad_cfg = v;
+    if (const char* q = strstr(t, "tile128=")) if (sscanf(q + 8, "%d", &v) == 1 && v > 0) h->tune_tile128_min = v;
+    if (const char* q = strstr(t, "blocks=")) if (sscanf(q + 7, "%d", &v) == 1 && v > 0) h->tune_target_blocks = v;
+  }
   plan(h);
   *out = h;
   return BETTY_OK;

@@ -288,8 +288,10 @@ __device__ void bias_rows(const BiasJob& j, int row) {
   }
 }
 
+// (128-tiles are compiled for two resident workgroups per compute unit, so that one workgroup's
+// epilogue traffic overlaps the other's k loop)
 template <typename T, int BM, int BN, int NCH, int WPG, int KG, int MODE>
-__global__ __launch_bounds__(64 * WPG * KG) void gemm_fused_kernel(GemmBatch batch) {
+__global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void gemm_fused_kernel(GemmBatch batch) {
   constexpr int GT = 64 * WPG;                     // threads of one K group
   constexpr int WM = WPG == 4 ? 2 : 1, WN = WPG == 4 ? 2 : 1;   // wavefronts of a group over the tile
   constexpr int ROW = NCH + 1;                     // LDS row pitch in 16-byte chunks
@@ -341,7 +343,7 @@ __global__ __launch_bounds__(64 * WPG * KG) void gemm_fused_kernel(GemmBatch bat
   // epilogue inputs of this wavefront's blocks: requested now, consumed after the k loop.  Only
   // group 0 finishes the tile.  (With several blocks per wavefront the prefetch is kept for the
   // parameter-shaped modes, whose epilogue moves far more bytes than their k loop.)
-  constexpr bool PREFETCH = TM * TN == 1 || MODE >= EPI_WGRAD;
+  constexpr bool PREFETCH = TM * TN == 1 || (MODE >= EPI_WGRAD && BM == 64);
   const Epilogue& e = batch.p[pi].e;
   EpiRegs pre[TM * TN];
   if constexpr (PREFETCH) {
