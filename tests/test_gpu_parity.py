@@ -251,3 +251,25 @@ def test_graph_replays_match_first_direct_run(kind):
     ref = orc.hypergrad_neumann(oracle_problem(wl), wl.w, wl.lam, 2, 0.05)
     assert rel_l2(host(got), ref) < 2e-2
     b.close()
+
+
+def test_more_than_eight_layers_and_unequal_batches():
+    """Ten layers exercise the chunking of the grouped launches (eight problems per launch);
+    train and validation batches of different padded sizes share their launches."""
+    dims = (20, 24, 16, 24, 16, 24, 16, 24, 16, 24, 5)
+    wl = wk.tiny(kind="l2", act="gelu", dims=dims, batch=150)      # val batch = 152 -> pads to 256, train 150 -> 256
+    run_all(wl)
+    wl2 = wk.tiny(kind="reweight", act="relu", dims=dims, batch=127, prec="bf16", hidden=17)   # 127 / 129: pads 128 / 256
+    run_all(wl2)
+
+
+def test_single_sample_and_no_bias():
+    wl = wk.tiny(kind="l2", act="gelu", dims=(7, 5, 3), batch=1, has_bias=False)
+    run_all(wl)
+
+
+def test_single_layer_softmax_regression():
+    wl = wk.tiny(kind="l2", act="none", loss="ce", dims=(40, 6), batch=33)
+    run_all(wl, big_alpha=0.3)
+    wl = wk.tiny(kind="reweight", act="none", loss="ce", dims=(40, 6), batch=33, hidden=8)
+    run_all(wl)
