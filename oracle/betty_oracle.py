@@ -21,6 +21,7 @@ project's stated reading of them:
 
   Neumann(K, alpha):  v_0 = p_0 = g;  v_k = v_{k-1} - alpha H v_{k-1};
                       p_k = p_{k-1} + v_k;  q = alpha p_K   (K products, K+1 terms)
+  CG(K):              K conjugate-gradient iterations on H q = g from q = 0
   FD(K, alpha, s):    the same with  H v := [grad L_L(w + e v) - grad L_L(w - e v)] / (2 e),
                       e = s / ||v||_2, and the mixed term by the same central
                       difference of grad_lambda L_L along q.  K = 0 is the
@@ -244,12 +245,12 @@ def backprop(prob: Problem, w, a, zs, deltaL):
     return join_params(prob, grads)
 
 
-def data_cost_and_grad(prob: Problem, w, lam, which):
+def data_cost_and_grad(prob: Problem, w, lam, which, ell_frozen=None):
     lower = which == "train"
     X, target = prob.batch(which)
     a, zs = forward(prob, w, X)
     ell, dz = sample_losses(prob, zs[-1], target)
-    s = sample_scales(prob, ell, lam, lower)
+    s = sample_scales(prob, ell if ell_frozen is None else ell_frozen, lam, lower)
     cost = float((s * ell).sum())
     grad = backprop(prob, w, a, zs, s[:, None] * dz)
     return cost, grad
@@ -268,10 +269,13 @@ def lower_cost(prob: Problem, w, lam):
     return cost
 
 
-def lower_grad(prob: Problem, w, lam):
-    """(L_L, grad_w L_L) on the train batch; the reweighting weights are constants in w."""
+def lower_grad(prob: Problem, w, lam, ell_frozen=None):
+    """(L_L, grad_w L_L) on the train batch; the reweighting weights are constants in w.
+
+    ell_frozen, if given, is the per-sample loss fed to the weight net instead of l_i(w)
+    (used by the finite-difference products, which must keep the weights fixed)."""
     w = np.asarray(w, dtype=F64)
-    cost, grad = data_cost_and_grad(prob, w, lam, "train")
+    cost, grad = data_cost_and_grad(prob, w, lam, "train", ell_frozen)
     if prob.hp == "l2":
         e = np.exp(np.asarray(lam, dtype=F64))
         cost += float((e * w * w).sum())
@@ -337,16 +341,27 @@ def hvp(prob: Problem, w, lam, v):
     return Hv
 
 
+def train_losses(prob: Problem, w):
+    """l_i(w) on the train batch."""
+    X, target = prob.batch("train")
+    _, zs = forward(prob, np.asarray(w, dtype=F64), X)
+    return sample_losses(prob, zs[-1], target)[0]
+
+
 def hvp_fd(prob: Problem, w, lam, v, eps_scale):
-    """Central finite difference of the lower gradient along v, step eps_scale/||v||_2."""
+    """Central finite difference of the lower gradient along v, step eps_scale/||v||_2.
+
+    For the reweighting cost the sample weights stay those of the unperturbed w (the cost treats
+    them as constants in w), so that the difference approximates the same H as `hvp`."""
     w = np.asarray(w, dtype=F64)
     v = np.asarray(v, dtype=F64)
     nrm = float(np.sqrt((v * v).sum()))
     if nrm == 0.0:
         return np.zeros_like(v)
     eps = eps_scale / nrm
-    gp = lower_grad(prob, w + eps * v, lam)[1]
-    gm = lower_grad(prob, w - eps * v, lam)[1]
+    frozen = train_losses(prob, w) if prob.hp == "reweight" else None
+    gp = lower_grad(prob, w + eps * v, lam, frozen)[1]
+    gm = lower_grad(prob, w - eps * v, lam, frozen)[1]
     return (gp - gm) / (2.0 * eps)
 
 
@@ -437,6 +452,36 @@ def hypergrad_fd(prob: Problem, w, lam, K, alpha, eps_scale):
     g = upper_grad(prob, w)[1]
     q = neumann_q(prob, w, lam, g, K, alpha, lambda v: hvp_fd(prob, w, lam, v, eps_scale))
     return mixed_vjp_fd(prob, w, lam, q, eps_scale)
+
+
+def cg_q(g, K, product):
+    """K conjugate-gradient iterations on H q = g from q = 0 (AID-CG, Sec. 3.2)."""
+    g = np.asarray(g, dtype=F64)
+    q = np.zeros_like(g)
+    r = g.copy()
+    d = r.copy()
+    rs = float(r @ r)
+    for _ in range(K):
+        if rs == 0.0:
+            break
+        Hd = product(d)
+        dHd = float(d @ Hd)
+        if dHd == 0.0:
+            break
+        a = rs / dHd
+        q = q + a * d
+        r = r - a * Hd
+        rs_new = float(r @ r)
+        d = r + (rs_new / rs) * d
+        rs = rs_new
+    return q
+
+
+def hypergrad_cg(prob: Problem, w, lam, K):
+    """dL_U/dlambda with H^{-1} g approximated by K conjugate-gradient iterations."""
+    g = upper_grad(prob, w)[1]
+    q = cg_q(g, K, lambda v: hvp(prob, w, lam, v))
+    return mixed_vjp(prob, w, lam, q)
 
 
 # ----------------------------------------------------------------------------

@@ -482,3 +482,46 @@ def test_workload_labels_follow_the_noise_rule():
     assert (out == wl.y_tr).all()
     assert 0.25 < mask.mean() < 0.55
     assert wl.d == 792586 and wk.config(2).d == 203530
+
+
+# ---------------------------------------------------------------- conjugate-gradient variant
+
+def test_cg_on_ridge_converges_to_closed_form_and_is_krylov_optimal():
+    wl, prob, lam, w_star = ridge_setup()
+    full, H, g = ridge_closed_form(wl, lam, w_star)
+    # d = 64: exact in at most 64 steps (well before, given the clustered spectrum)
+    assert rel_l2(orc.hypergrad_cg(prob, w_star, lam, 64), full) < 1e-10
+    # after K steps q_K minimises 0.5 q'Hq - g'q over span{g, Hg, ..., H^(K-1) g}
+    for K in (1, 3, 6):
+        basis = [g]
+        for _ in range(K - 1):
+            basis.append(H @ basis[-1])
+        Q, _ = np.linalg.qr(np.array(basis).T)
+        qK = Q @ np.linalg.solve(Q.T @ H @ Q, Q.T @ g)
+        got = orc.cg_q(g, K, lambda v: orc.hvp(prob, w_star, lam, v))
+        assert rel_l2(got, qK) < 1e-9
+    assert not orc.cg_q(g, 0, lambda v: H @ v).any()
+    assert not orc.cg_q(np.zeros_like(g), 5, lambda v: H @ v).any()
+
+
+@pytest.mark.parametrize("cfg", [TINY[0], dict(kind="l2", act="none", loss="ce", dims=(5, 4), batch=11)])
+def test_cg_on_tiny_mlp_matches_dense_solve(cfg):
+    wl = wk.tiny(**cfg)
+    wl.lam = (wl.lam + 3.0).astype(np.float32)          # strong decay: H positive definite
+    prob = oracle_problem(wl)
+    H = dense_hessian_by_hvp(prob, wl.w, wl.lam)
+    assert np.linalg.eigvalsh(H).min() > 0
+    g = orc.upper_grad(prob, wl.w)[1]
+    expect = orc.mixed_vjp(prob, wl.w, wl.lam, np.linalg.solve(H, g))
+    assert rel_l2(orc.hypergrad_cg(prob, wl.w, wl.lam, wl.d), expect) < 1e-8
+
+
+def test_fd_product_keeps_reweighting_weights_frozen():
+    wl = wk.tiny(kind="reweight", act="gelu", loss="ce")
+    prob = oracle_problem(wl)
+    v = _vec(12, wl.d)
+    Hv = orc.hvp(prob, wl.w, wl.lam, v)
+    assert rel_l2(orc.hvp_fd(prob, wl.w, wl.lam, v, 0.01), Hv) < 1e-3
+    assert rel_l2(orc.hvp_fd(prob, wl.w, wl.lam, v, 1e-4), Hv) < 1e-6
+    got = orc.hypergrad_fd(prob, wl.w, wl.lam, 3, 0.05, 0.01)
+    assert rel_l2(got, orc.hypergrad_neumann(prob, wl.w, wl.lam, 3, 0.05)) < 1e-3
