@@ -141,9 +141,17 @@ betty_status betty_hypergrad_neumann(betty_handle h, const float* w, const float
  *   H v := [grad_w L_L(w + e v) - grad_w L_L(w - e v)] / (2 e),  e = eps_scale / ||v||_2,
  * and the mixed term by the same central difference of grad_lambda L_L along q.  Only
  * first-order gradients are evaluated; K = 0 gives q = alpha g.  fp32 operands throughout.
- * BETTY_HP_REWEIGHT_NET is not implemented for this variant (BETTY_EUNSUPPORTED). */
+ * For BETTY_HP_REWEIGHT_NET the sample weights and the loss values fed to the weight net are
+ * those of the unperturbed w in every perturbed evaluation (the cost holds them constant in w). */
 betty_status betty_hypergrad_fd(betty_handle h, const float* w, const float* lambda, int K,
                                 float alpha, float eps_scale, float* dlambda);
+
+/* Conjugate-gradient hypergradient (AID-CG, Sec. 3.2): K conjugate-gradient iterations on
+ * H q = g from q = 0 with g = grad_w L_U(w), then dlambda = betty_mixed_vjp(q).  K >= 0.
+ * H must be positive definite for the iteration to be meaningful; a zero curvature d'Hd or a
+ * zero residual freezes the iterate (no division by zero). */
+betty_status betty_hypergrad_cg(betty_handle h, const float* w, const float* lambda, int K,
+                                float* dlambda);
 
 /* Uniform label noise as integer work: T = floor(p * 2^32);
  *   mask_i = words_i < T;  y_out_i = mask_i ? alt_i : y_i.   n >= 0 elements, p in [0, 1].

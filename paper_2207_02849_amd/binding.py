@@ -79,12 +79,13 @@ def load_library():
     lib.betty_mixed_vjp.argtypes = [vp, f32p, f32p, f32p, f32p]
     lib.betty_hypergrad_neumann.argtypes = [vp, f32p, f32p, C.c_int, C.c_float, f32p]
     lib.betty_hypergrad_fd.argtypes = [vp, f32p, f32p, C.c_int, C.c_float, C.c_float, f32p]
+    lib.betty_hypergrad_cg.argtypes = [vp, f32p, f32p, C.c_int, f32p]
     lib.betty_apply_label_noise.argtypes = [vp, vp, vp, vp, C.c_double, C.c_int, vp, vp]
     lib.betty_profile_enable.argtypes = [vp, C.c_int]
     lib.betty_profile_collect.argtypes = [vp]
     lib.betty_profile_get.argtypes = [vp, C.c_int, C.POINTER(ProfileRec)]
     for name in ("betty_lower_grad", "betty_upper_grad", "betty_hvp", "betty_mixed_vjp",
-                 "betty_hypergrad_neumann", "betty_hypergrad_fd", "betty_apply_label_noise",
+                 "betty_hypergrad_neumann", "betty_hypergrad_fd", "betty_hypergrad_cg", "betty_apply_label_noise",
                  "betty_profile_enable", "betty_profile_collect", "betty_profile_get"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -193,6 +194,13 @@ class Betty:
         self._check(self.lib.betty_hypergrad_fd(self.h, _ptr(w, torch.float32, self.d),
                                                 _ptr(lam, torch.float32, self.n_hyper), int(K), float(alpha),
                                                 float(eps_scale), _ptr(o, torch.float32, self.n_hyper)))
+        return o
+
+    def betty_hypergrad_cg(self, w, lam, K, out=None):
+        o = out if out is not None else self._vec(self.n_hyper)
+        self._check(self.lib.betty_hypergrad_cg(self.h, _ptr(w, torch.float32, self.d),
+                                                _ptr(lam, torch.float32, self.n_hyper), int(K),
+                                                _ptr(o, torch.float32, self.n_hyper)))
         return o
 
     def betty_apply_label_noise(self, y, words, alt, p, want_mask=True):

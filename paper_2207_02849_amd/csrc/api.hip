@@ -46,6 +46,7 @@ struct SideBuf {
   std::vector<size_t> A, At, D, Dt;           // a_l (1..L-1), delta_l (1..L), each in both orientations
   std::vector<size_t> dphi, e2;               // fp32 phi'(z_l); phi''(z_l) then (delta W^T) phi''
   size_t ZL = 0, P = 0, ell = 0, s = 0, omega = 0;
+  size_t ell_bar = 0, omega_bar = 0, ell_p = 0;   // frozen / perturbed per-sample values (finite differences, reweighting)
 };
 
 // One complete set of GEMM operands in a given element type.
@@ -84,7 +85,7 @@ struct betty_handle_s {
     int K = -1; float alpha = 0.f, eps = 0.f;
     int seen = 0;
   };
-  GraphSlot graph_neumann, graph_fd;
+  GraphSlot graph_neumann, graph_fd, graph_cg;
   bool use_graphs = true;
   int tune_target_blocks = 256, tune_tile128_min = 512;   // see plan_chain (measured on 512x4096x8192: 64-tiles beat 128-tiles until the grid is several waves deep)
   int tune_wgrad_cfg = GEMM_64x1;
@@ -141,6 +142,9 @@ void plan_side(betty_handle h, Planner& pl, SideBuf& sb, Elem elem, int B, bool 
   sb.ell = pl.take(Bp * 4);
   sb.s = pl.take(Bp * 4);
   sb.omega = pl.take(Bp * 4);
+  sb.ell_bar = pl.take(Bp * 4);
+  sb.omega_bar = pl.take(Bp * 4);
+  sb.ell_p = pl.take(Bp * 4);
 }
 
 void plan_set(betty_handle h, Planner& pl, OperandSet& os, Elem elem) {
@@ -261,7 +265,8 @@ enum { SIDE_TRAIN = 1, SIDE_VAL = 2, SIDE_BOTH = 3 };
 inline bool has_side(int mask, int side) { return (mask >> side) & 1; }
 
 // a_l, phi'(z_l) (and phi'' on the lower side), logits, per-sample loss, output delta
-void forward_and_loss(betty_handle h, OperandSet& os, int sides, const float* w, const float* theta) {
+void forward_and_loss(betty_handle h, OperandSet& os, int sides, const float* w, const float* theta,
+                      const float* omega_fixed = nullptr) {
   const int L = h->L;
   const bool hybrid = hybrid_forward(h, os);
   OperandSet& fs = hybrid ? h->sets[1] : os;          // operands of the forward products
@@ -319,6 +324,7 @@ void forward_and_loss(betty_handle h, OperandSet& os, int sides, const float* w,
     a.Z = h->f(sb.ZL); a.ldz = lo.n_out_p;
     a.y = h->batch[side].y; a.target = h->batch[side].target; a.C = lo.n_out;
     a.theta = theta;
+    a.omega_fixed = side == 0 ? omega_fixed : nullptr;
     a.rows = sb.B; a.inv_batch = 1.0f / (float)sb.B;
     a.ell = h->f(sb.ell); a.s = h->f(sb.s); a.omega = h->f(sb.omega);
     a.P = h->f(sb.P);
@@ -482,9 +488,9 @@ void hvp_cached(betty_handle h, OperandSet& os, const float* vflat, const WgradS
 
 // full first-order gradient of the lower cost at w (operand copies of w already made)
 void lower_grad_seq(betty_handle h, OperandSet& os, const float* w, const float* lam, float* grad,
-                    float* loss_or_null) {
+                    float* loss_or_null, const float* omega_fixed = nullptr) {
   const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
-  forward_and_loss(h, os, SIDE_TRAIN, w, l2 ? nullptr : lam);
+  forward_and_loss(h, os, SIDE_TRAIN, w, l2 ? nullptr : lam, omega_fixed);
   backward_chain(h, os, SIDE_TRAIN);
   WgradSink k{EPI_WGRAD, grad, l2 ? lam : nullptr, l2 ? w : nullptr, nullptr, nullptr, 0.f, false};
   wgrad_batch(h, os, 0, false, k);
@@ -577,7 +583,7 @@ static void drop_graph(betty_handle_s::GraphSlot& g) {
   g = betty_handle_s::GraphSlot();
 }
 
-static void drop_graphs(betty_handle h) { drop_graph(h->graph_neumann); drop_graph(h->graph_fd); }
+static void drop_graphs(betty_handle h) { drop_graph(h->graph_neumann); drop_graph(h->graph_fd); drop_graph(h->graph_cg); }
 
 // Runs `body` (which only enqueues kernels on the bound stream) directly the first time a given
 // argument set is seen, captures it into a graph the second time, and replays the graph from then
@@ -830,32 +836,89 @@ betty_status betty_hypergrad_fd(betty_handle h, const float* w, const float* lam
                                 float eps_scale, float* dlambda) {
   CHECK(check_hyper_args(h, w, lambda, K, alpha, dlambda));
   if (!std::isfinite(eps_scale) || eps_scale <= 0.f) return fail(h, BETTY_EINVAL, "eps_scale must be positive and finite");
-  if (h->desc.hp != BETTY_HP_L2_DECAY)
-    return fail(h, BETTY_EUNSUPPORTED, "finite-difference variant is implemented for L2-decay hyperparameters only");
   auto body = [=]() {
     OperandSet& os = fd_operands(h);
+    SideBuf& sb = os.side[0];
+    const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
     float* v = h->f(h->vec_v); float* p = h->f(h->vec_p); float* Gp = h->f(h->vec_Hv);
     float* Gm = h->f(h->vec_Gm); float* wpm = h->f(h->vec_wpm);
     float* nrm2 = h->f(h->scalars); float* eps = h->f(h->scalars) + 1;
     make_weight_operands(h, os, w);
     WgradSink init{EPI_WGRAD_INIT, nullptr, nullptr, nullptr, v, p, 0.f, false};
-    upper_grad_seq(h, os, w, nullptr, false, init, nullptr);
+    const float* omega_bar = nullptr;
+    if (l2) {
+      upper_grad_seq(h, os, w, nullptr, false, init, nullptr);
+    } else {
+      // the reweighting cost holds its sample weights constant in w: evaluate them (and the loss fed
+      // to the weight net) once at the unperturbed w and keep them for every perturbed pass
+      forward_and_loss(h, os, SIDE_BOTH, w, lambda);
+      backward_chain(h, os, SIDE_VAL);
+      wgrad_batch(h, os, 1, false, init);
+      launch_scale_copy(h->ctx, h->f(sb.ell), 1.f, h->f(sb.ell_bar), sb.B);
+      launch_scale_copy(h->ctx, h->f(sb.omega), 1.f, h->f(sb.omega_bar), sb.B);
+      omega_bar = h->f(sb.omega_bar);
+    }
     for (int k = 0; k < K; ++k) {
       launch_sumsq(h->ctx, v, h->d, h->at<double>(h->partials), nrm2);
       launch_fd_eps(h->ctx, nrm2, eps_scale, 1.f, eps);
       launch_fd_perturb(h->ctx, w, v, eps, +1.f, wpm, h->d);
       make_weight_operands(h, os, wpm);
-      lower_grad_seq(h, os, wpm, lambda, Gp, nullptr);
+      lower_grad_seq(h, os, wpm, lambda, Gp, nullptr, omega_bar);
       launch_fd_perturb(h->ctx, w, v, eps, -1.f, wpm, h->d);
       make_weight_operands(h, os, wpm);
-      lower_grad_seq(h, os, wpm, lambda, Gm, nullptr);
+      lower_grad_seq(h, os, wpm, lambda, Gm, nullptr, omega_bar);
       launch_fd_update(h->ctx, v, p, Gp, Gm, eps, alpha, h->d);
     }
     launch_sumsq(h->ctx, p, h->d, h->at<double>(h->partials), nrm2);
     launch_fd_eps(h->ctx, nrm2, eps_scale, alpha, eps);
-    launch_mixed_l2_fd(h->ctx, lambda, w, p, alpha, eps, dlambda, h->d);
+    if (l2) {
+      launch_mixed_l2_fd(h->ctx, lambda, w, p, alpha, eps, dlambda, h->d);
+    } else {
+      // grad_theta L_L(w') = (1/B) sum_i l_i(w') dR(lbar_i)/dtheta, so its central difference along
+      // q = alpha p needs only the per-sample losses at w +- eps q
+      launch_scale_copy(h->ctx, p, alpha, v, h->d);                       // v := q (v is no longer needed)
+      launch_fd_perturb(h->ctx, w, v, eps, +1.f, wpm, h->d);
+      make_weight_operands(h, os, wpm);
+      forward_and_loss(h, os, SIDE_TRAIN, wpm, lambda, omega_bar);
+      launch_scale_copy(h->ctx, h->f(sb.ell), 1.f, h->f(sb.ell_p), sb.B);
+      launch_fd_perturb(h->ctx, w, v, eps, -1.f, wpm, h->d);
+      make_weight_operands(h, os, wpm);
+      forward_and_loss(h, os, SIDE_TRAIN, wpm, lambda, omega_bar);
+      launch_fd_loss_diff(h->ctx, h->f(sb.ell_p), h->f(sb.ell), eps, sb.B, h->f(os.cvec));
+      launch_wnet_theta_vjp(h->ctx, h->f(sb.ell_bar), h->f(sb.omega_bar), h->f(os.cvec), lambda,
+                            h->desc.wnet_hidden, sb.B, 1.0f / (float)sb.B, dlambda);
+    }
   };
   return run_cached(h, h->graph_fd, w, lambda, dlambda, K, alpha, eps_scale, body);
+}
+
+betty_status betty_hypergrad_cg(betty_handle h, const float* w, const float* lambda, int K, float* dlambda) {
+  CHECK(check_hyper_args(h, w, lambda, K, 0.f, dlambda));
+  auto body = [=]() {
+    OperandSet& os = h->sets[0];
+    const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
+    float* r = h->f(h->vec_g); float* d = h->f(h->vec_v); float* q = h->f(h->vec_p); float* Hd = h->f(h->vec_Hv);
+    float* sc = h->f(h->scalars);            // sc[0], sc[1]: r.r of the current / next iterate; sc[2]: d.Hd
+    double* partials = h->at<double>(h->partials);
+    make_weight_operands(h, os, w);
+    WgradSink g_out{EPI_WGRAD, r, nullptr, nullptr, nullptr, nullptr, 0.f, false};
+    upper_grad_seq(h, os, w, lambda, K > 0 || !l2, g_out, nullptr);
+    launch_cg_init(h->ctx, r, d, q, h->d);
+    launch_sumsq(h->ctx, r, h->d, partials, sc);
+    for (int k = 0; k < K; ++k) {
+      float* rs = sc + (k & 1);
+      float* rs_new = sc + ((k + 1) & 1);
+      make_shadows(h, os, d, 1.f, &os.Vn, &os.Vt);
+      WgradSink hd{EPI_WGRAD, Hd, l2 ? lambda : nullptr, l2 ? d : nullptr, nullptr, nullptr, 0.f, false};
+      hvp_cached(h, os, d, hd);
+      launch_dot(h->ctx, d, Hd, h->d, partials, sc + 2);
+      launch_cg_step(h->ctx, q, r, d, Hd, rs, sc + 2, h->d, partials, rs_new);
+      if (k + 1 < K) launch_cg_dir(h->ctx, d, r, rs, rs_new, h->d);
+    }
+    if (l2) launch_mixed_l2(h->ctx, lambda, w, q, 1.f, dlambda, h->d);
+    else mixed_reweight_seq(h, os, lambda, q, 1.f, dlambda);
+  };
+  return run_cached(h, h->graph_cg, w, lambda, dlambda, K, 0.f, -1.f, body);
 }
 
 betty_status betty_apply_label_noise(betty_handle h, const int32_t* y, const uint32_t* words, const int32_t* alt,

@@ -127,6 +127,7 @@ struct LossArgs {
   const float* Z; long long ldz;        // logits [rows][ldz]
   const int32_t* y; const float* target; int C;
   const float* theta;                   // weight net (reweight only)
+  const float* omega_fixed;             // reweight only: use these weights instead of R(l_i; theta)
   int rows; float inv_batch;
   float* ell; float* s; float* omega;   // per-sample outputs
   float* P;                             // softmax probabilities [rows][ldz] (CE)
@@ -150,6 +151,15 @@ void launch_fill_zero(Ctx&, void* p, size_t bytes);
 void launch_scale_copy(Ctx&, const float* src, float scale, float* dst, size_t n);
 void launch_mixed_l2(Ctx&, const float* lam, const float* w, const float* p, float alpha, float* out, size_t n);
 void launch_sumsq(Ctx&, const float* x, size_t n, double* partials, float* out_scalar);
+void launch_dot(Ctx&, const float* x, const float* y, size_t n, double* partials, float* out_scalar);
+// conjugate gradient on device scalars: a = rs / dHd (0 if either is 0); q += a d; r -= a Hd; rs_new = r.r
+void launch_cg_init(Ctx&, const float* r, float* d, float* q, size_t n);
+void launch_cg_step(Ctx&, float* q, float* r, const float* d, const float* Hd, const float* rs, const float* dHd,
+                    size_t n, double* partials, float* rs_new);
+// d = r + (rs_new / rs) d   (beta = 0 if rs == 0)
+void launch_cg_dir(Ctx&, float* d, const float* r, const float* rs, const float* rs_new, size_t n);
+// c_i = (lp_i - lm_i) / (2 eps)   (0 if eps == 0)
+void launch_fd_loss_diff(Ctx&, const float* lp, const float* lm, const float* eps_dev, int rows, float* c);
 void launch_l2_cost(Ctx&, const float* lam, const float* w, size_t n, double* partials, float* out_scalar);
 void launch_weighted_loss_sum(Ctx&, const float* s, const float* ell, int rows, const float* add_or_null, float* out);
 // eps_dev = eps_scale / sqrt(nrm2) (0 if nrm2 == 0);  out = w + sign * eps_dev * scale * v

@@ -131,7 +131,9 @@ __global__ __launch_bounds__(256) void loss_rows_kernel(LossBatch lb) {
     ell = wave_sum(acc);
   }
   float omega = 1.f;
-  if (a.reweight) {
+  if (a.reweight && a.omega_fixed) {
+    omega = a.omega_fixed[row];
+  } else if (a.reweight) {
     const int H = a.hidden;
     float part = 0.f;
     for (int j = lane; j < H; j += 64)
@@ -321,7 +323,7 @@ void launch_mixed_l2(Ctx& ctx, const float* lam, const float* w, const float* p,
 // two-stage deterministic reductions: per-block partials, then one block in fixed order
 constexpr int RED_BLOCKS = 1024;
 
-template <int MODE>   // 0: sum x^2   1: sum exp(lam) x^2
+template <int MODE>   // 0: sum x^2   1: sum exp(lam) x^2   2: sum lam x  (lam = second vector)
 __global__ __launch_bounds__(256) void reduce_stage1_kernel(const float* lam, const float* x, size_t n, double* partials) {
   __shared__ double red[4];
   float acc = 0.f;
@@ -329,7 +331,7 @@ __global__ __launch_bounds__(256) void reduce_stage1_kernel(const float* lam, co
   int cnt = 0;
   FLAT_LOOP(i, n) {
     const float xi = x[i];
-    acc += MODE == 0 ? xi * xi : expf(lam[i]) * xi * xi;
+    acc += MODE == 0 ? xi * xi : MODE == 1 ? expf(lam[i]) * xi * xi : lam[i] * xi;
     if (++cnt == 64) { dacc += acc; acc = 0.f; cnt = 0; }
   }
   dacc += acc;
@@ -351,7 +353,8 @@ static void launch_reduce(Ctx& ctx, int mode, const float* lam, const float* x, 
   {
     Launch l(ctx, BETTY_K_REDUCE, 0, (mode ? 8.0 : 4.0) * n);
     if (mode == 0) reduce_stage1_kernel<0><<<nb, 256, 0, ctx.stream>>>(lam, x, n, partials);
-    else reduce_stage1_kernel<1><<<nb, 256, 0, ctx.stream>>>(lam, x, n, partials);
+    else if (mode == 1) reduce_stage1_kernel<1><<<nb, 256, 0, ctx.stream>>>(lam, x, n, partials);
+    else reduce_stage1_kernel<2><<<nb, 256, 0, ctx.stream>>>(lam, x, n, partials);
   }
   {
     Launch l(ctx, BETTY_K_REDUCE);
@@ -363,6 +366,73 @@ void launch_sumsq(Ctx& ctx, const float* x, size_t n, double* partials, float* o
 }
 void launch_l2_cost(Ctx& ctx, const float* lam, const float* w, size_t n, double* partials, float* out) {
   launch_reduce(ctx, 1, lam, w, n, partials, out);
+}
+void launch_dot(Ctx& ctx, const float* x, const float* y, size_t n, double* partials, float* out) {
+  launch_reduce(ctx, 2, y, x, n, partials, out);
+}
+
+// ---- conjugate gradient (scalars stay on the device; nothing here reads them on the host)
+__global__ __launch_bounds__(256) void cg_init_kernel(const float* r, float* d, float* q, size_t n) {
+  FLAT_LOOP(i, n) { d[i] = r[i]; q[i] = 0.f; }
+}
+void launch_cg_init(Ctx& ctx, const float* r, float* d, float* q, size_t n) {
+  Launch l(ctx, BETTY_K_VECTOR, 0, 12.0 * n);
+  cg_init_kernel<<<flat_grid(n), 256, 0, ctx.stream>>>(r, d, q, n);
+}
+
+__global__ __launch_bounds__(256) void cg_step_kernel(float* q, float* r, const float* d, const float* Hd,
+                                                      const float* rs, const float* dHd, size_t n, double* partials) {
+  __shared__ double red[4];
+  const float num = rs[0], den = dHd[0];
+  const float a = (num != 0.f && den != 0.f) ? num / den : 0.f;
+  float acc = 0.f;
+  double dacc = 0.0;
+  int cnt = 0;
+  FLAT_LOOP(i, n) {
+    q[i] += a * d[i];
+    const float ri = r[i] - a * Hd[i];
+    r[i] = ri;
+    acc += ri * ri;
+    if (++cnt == 64) { dacc += acc; acc = 0.f; cnt = 0; }
+  }
+  dacc += acc;
+  dacc = block_sum(dacc, red);
+  if (threadIdx.x == 0) partials[blockIdx.x] = dacc;
+}
+void launch_cg_step(Ctx& ctx, float* q, float* r, const float* d, const float* Hd, const float* rs, const float* dHd,
+                    size_t n, double* partials, float* rs_new) {
+  unsigned nb = flat_grid(n);
+  if (nb > RED_BLOCKS) nb = RED_BLOCKS;
+  {
+    Launch l(ctx, BETTY_K_VECTOR, 0, 24.0 * n);
+    cg_step_kernel<<<nb, 256, 0, ctx.stream>>>(q, r, d, Hd, rs, dHd, n, partials);
+  }
+  {
+    Launch l(ctx, BETTY_K_REDUCE);
+    reduce_stage2_kernel<<<1, 256, 0, ctx.stream>>>(partials, (int)nb, rs_new);
+  }
+}
+
+__global__ __launch_bounds__(256) void cg_dir_kernel(float* d, const float* r, const float* rs, const float* rs_new, size_t n) {
+  const float den = rs[0];
+  const float beta = den != 0.f ? rs_new[0] / den : 0.f;
+  FLAT_LOOP(i, n) d[i] = r[i] + beta * d[i];
+}
+void launch_cg_dir(Ctx& ctx, float* d, const float* r, const float* rs, const float* rs_new, size_t n) {
+  Launch l(ctx, BETTY_K_VECTOR, 0, 12.0 * n);
+  cg_dir_kernel<<<flat_grid(n), 256, 0, ctx.stream>>>(d, r, rs, rs_new, n);
+}
+
+__global__ __launch_bounds__(256) void fd_loss_diff_kernel(const float* lp, const float* lm, const float* eps_dev, int rows, float* c) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= rows) return;
+  const float e = eps_dev[0];
+  c[i] = e > 0.f ? (lp[i] - lm[i]) / (2.f * e) : 0.f;
+}
+void launch_fd_loss_diff(Ctx& ctx, const float* lp, const float* lm, const float* eps_dev, int rows, float* c) {
+  if (rows <= 0) return;
+  Launch l(ctx, BETTY_K_OTHER);
+  fd_loss_diff_kernel<<<(rows + 255) / 256, 256, 0, ctx.stream>>>(lp, lm, eps_dev, rows, c);
 }
 
 __global__ __launch_bounds__(256) void weighted_loss_sum_kernel(const float* s, const float* ell, int rows, const float* add, float* out) {

@@ -69,7 +69,10 @@ def run_all(wl, tol=None, fd=True, big_alpha=None, check_losses=True, stationary
         hgb = b.betty_hypergrad_neumann(w, lam, wl.K, big_alpha)
         errs["neumann_big_alpha"] = rel_l2(host(hgb), orc.hypergrad_neumann(prob, w64, lam64, wl.K, big_alpha))
 
-    if fd and wl.hp == "l2":
+    hc = b.betty_hypergrad_cg(w, lam, 3)
+    errs["cg"] = rel_l2(host(hc), orc.hypergrad_cg(prob, w64, lam64, 3))
+
+    if fd:
         hf = b.betty_hypergrad_fd(w, lam, wl.K, wl.alpha, wl.eps_scale)
         errs["fd"] = rel_l2(host(hf), orc.hypergrad_fd(prob, w64, lam64, wl.K, wl.alpha, wl.eps_scale))
         hf0 = b.betty_hypergrad_fd(w, lam, 0, wl.alpha, wl.eps_scale)
@@ -83,6 +86,10 @@ def run_all(wl, tol=None, fd=True, big_alpha=None, check_losses=True, stationary
     print(wl.name, {k: f"{e:.2e}" for k, e in errs.items()}, flush=True)
     for k, e in errs.items():
         limit = 1e-4 if k.startswith("fd") else tol       # the FD variant always runs fp32 operands
+        if k == "cg" and wl.prec == "bf16":
+            # CG step lengths are ratios r.r / d.Hd; at an untrained w the lower Hessian is indefinite,
+            # d.Hd can be small and the ratio amplifies the operand rounding of the bf16 products
+            limit = 5e-2
         assert e < limit, (wl.name, k, e)
     return errs
 
@@ -200,11 +207,11 @@ def test_argument_errors_leave_outputs_untouched():
     assert e.value.status == binding.EINVAL
     torch.cuda.synchronize()
     assert (out == 7.0).all()
-    wl2 = wk.tiny(kind="reweight")
-    b2 = binding.from_workload(wl2)
     with pytest.raises(binding.BettyError) as e:
-        b2.betty_hypergrad_fd(dev(wl2.w), dev(wl2.lam), 1, 0.1)
-    assert e.value.status == binding.EUNSUPPORTED
+        b.betty_hypergrad_cg(w, lam, -2, out=out)
+    assert e.value.status == binding.EINVAL
+    torch.cuda.synchronize()
+    assert (out == 7.0).all()
 
 
 def test_zero_direction_and_fd_zero_gradient():
