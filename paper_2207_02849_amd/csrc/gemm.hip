@@ -377,10 +377,14 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
   }
   // one k-tile: registers -> LDS, refill the registers two tiles ahead, multiply.  Every thread
   // of the workgroup passes both barriers whether or not its group still has a tile (t_ < te).
-#define BETTY_STAGE(RA_, RB_, t_, first_)                                                            \
+  // In the steady-state loop the refill is unconditional (always_), so the loop body has no branch
+  // around memory instructions: the compiler then knows exactly how many loads are in flight and
+  // waits only for the register set it is about to store.  The last stages refill conditionally.
+#define BETTY_STAGE(RA_, RB_, t_, first_, always_)                                                   \
   {                                                                                                  \
+    const bool live_ = KG == 1 || (t_) < te;                                                         \
     if (!(first_)) BETTY_GROUP_SYNC();                                                               \
-    if ((t_) < te) {                                                                                 \
+    if (live_) {                                                                                     \
       _Pragma("unroll") for (int i_ = 0; i_ < LA; ++i_) {                                            \
         const int idx_ = tid + i_ * GT;                                                              \
         sA[(idx_ / NCH) * ROW + idx_ % NCH] = RA_[i_];                                               \
@@ -391,8 +395,8 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
       }                                                                                              \
     }                                                                                                \
     BETTY_GROUP_SYNC();                                                                              \
-    if ((t_) + 2 < te) BETTY_GLOAD(RA_, RB_, (t_) + 2)                                               \
-    if ((t_) < te) {                                                                                 \
+    if ((always_) || (t_) + 2 < te) BETTY_GLOAD(RA_, RB_, (t_) + 2)                                  \
+    if (live_) {                                                                                     \
       _Pragma("unroll") for (int j_ = 0; j_ < NCH / 2; ++j_) {                                       \
         const int c_ = 2 * j_ + (lane >> 5);                                                         \
         u32x4 af_[TM], bf_[TN];                                                                      \
@@ -409,9 +413,21 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
 
   if (tb < te) BETTY_GLOAD(ra0, rb0, tb)
   if (tb + 1 < te) BETTY_GLOAD(ra1, rb1, tb + 1)
-  for (int it = 0; it < NI; it += 2) {
-    BETTY_STAGE(ra0, rb0, tb + it, it == 0)
-    if (it + 1 < NI) BETTY_STAGE(ra1, rb1, tb + it + 1, false)
+  // steady state while both refills of an iteration stay inside this group's k-range
+  const int n_full = te - tb;                       // tiles this group really has (<= NI)
+  int it = 0;
+  if (n_full > 3) {                                 // first pair peeled: no barrier before the first store
+    BETTY_STAGE(ra0, rb0, tb, true, true)
+    BETTY_STAGE(ra1, rb1, tb + 1, false, true)
+    it = 2;
+  }
+  for (; it + 3 < n_full; it += 2) {
+    BETTY_STAGE(ra0, rb0, tb + it, false, true)
+    BETTY_STAGE(ra1, rb1, tb + it + 1, false, true)
+  }
+  for (; it < NI; it += 2) {
+    BETTY_STAGE(ra0, rb0, tb + it, it == 0, false)
+    if (it + 1 < NI) BETTY_STAGE(ra1, rb1, tb + it + 1, false, false)
   }
 #undef BETTY_STAGE
 #undef BETTY_GLOAD
