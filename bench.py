@@ -118,6 +118,19 @@ def main():
     if wl.hp == "l2":
         t_fd = timed(lambda: b.betty_hypergrad_fd(w, lam, K, alpha, wl.eps_scale, out=out), n_side, 5)
 
+    # the step around the path (one unrolled lower SGD step, the hypergradient, one Adam step)
+    mom = torch.zeros_like(w)
+    am, av = torch.zeros(b.n_hyper, device="cuda"), torch.zeros(b.n_hyper, device="cuda")
+    w_work, lam_work = w.clone(), lam.clone()
+    counter = [0]
+
+    def bilevel():
+        counter[0] += 1
+        b.betty_lower_sgd_step(w_work, lam_work, mom, 1e-3, 0.9, 0.0)
+        b.betty_hypergrad_neumann(w_work, lam_work, K, alpha, out=out)
+        b.betty_upper_adam_step(lam_work, out, am, av, counter[0], 1e-5)
+    t_bilevel = timed(bilevel, n_side, 5)
+
     B = wl.X_tr.shape[0]
     grad_flops, hvp_flops = algorithmic_flops(wl.dims, B)
     t_hvp = (t_step - t_k0) / K if K > 0 else float("nan")
@@ -178,6 +191,8 @@ def main():
                            "avg_launch_us": (upd[1] / upd[0] * 1e3) if upd[0] else None},
         "phases": phases,
         "fd_hypergradients_per_s": (1.0 / t_fd) if t_fd else None,
+        "bilevel_upper_steps_per_s": {"value": 1.0 / t_bilevel,
+                                      "step": "1 lower momentum-SGD step + Neumann hypergradient + Adam step on lambda"},
     }
 
     if not args.no_cpu_baseline:

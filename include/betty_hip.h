@@ -153,6 +153,20 @@ betty_status betty_hypergrad_fd(betty_handle h, const float* w, const float* lam
 betty_status betty_hypergrad_cg(betty_handle h, const float* w, const float* lambda, int K,
                                 float* dlambda);
 
+/* ---- the optimisation steps around the path (Sec. 3.3; optimisers as in App. C) ----------- */
+
+/* One step of the lower problem, in place: momentum SGD on L_L(w, lambda) over the train batch,
+ *   g = grad_w L_L(w, lambda) + weight_decay * w;  momentum <- mu * momentum + g;  w <- w - lr * momentum.
+ * loss_or_null receives L_L at the w before the step.  Calling it `unroll` times and then a
+ * hypergradient call at the resulting w is the paper's unrolled lower optimisation. */
+betty_status betty_lower_sgd_step(betty_handle h, float* w, const float* lambda, float* momentum,
+                                  float lr, float mu, float weight_decay, float* loss_or_null);
+
+/* One Adam step on the upper parameters, in place, given their hypergradient; t >= 1 is the
+ * step counter of the bias correction; m, v are the moment buffers (length of lambda). */
+betty_status betty_upper_adam_step(betty_handle h, float* lambda, const float* dlambda, float* m,
+                                   float* v, int t, float lr, float beta1, float beta2, float eps);
+
 /* Uniform label noise as integer work: T = floor(p * 2^32);
  *   mask_i = words_i < T;  y_out_i = mask_i ? alt_i : y_i.   n >= 0 elements, p in [0, 1].
  * mask_or_null receives 0/1 bytes.  Runs on the handle's stream. */

@@ -485,6 +485,43 @@ def hypergrad_cg(prob: Problem, w, lam, K):
 
 
 # ----------------------------------------------------------------------------
+# the optimisation steps around the hypergradient (Sec. 3.3; optimisers as in App. C)
+# ----------------------------------------------------------------------------
+
+def lower_sgd_step(prob: Problem, w, lam, mom, lr, mu, weight_decay=0.0):
+    """One step of the lower problem: SGD with momentum on L_L(w, lambda) (+ plain weight decay).
+
+    g = grad_w L_L + weight_decay * w;  mom <- mu * mom + g;  w <- w - lr * mom."""
+    w = np.asarray(w, dtype=F64)
+    g = lower_grad(prob, w, lam)[1] + weight_decay * w
+    mom = mu * np.asarray(mom, dtype=F64) + g
+    return w - lr * mom, mom
+
+
+def adam_step(x, grad, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8):
+    """One Adam step (step counter t >= 1) on the upper parameters given their (hyper)gradient."""
+    x = np.asarray(x, dtype=F64)
+    grad = np.asarray(grad, dtype=F64)
+    m = beta1 * np.asarray(m, dtype=F64) + (1.0 - beta1) * grad
+    v = beta2 * np.asarray(v, dtype=F64) + (1.0 - beta2) * grad * grad
+    mhat = m / (1.0 - beta1 ** t)
+    vhat = v / (1.0 - beta2 ** t)
+    return x - lr * mhat / (np.sqrt(vhat) + eps), m, v
+
+
+def bilevel_step(prob: Problem, w, mom, lam, am, av, t, unroll, lr_w, mu, K, alpha, lr_lam,
+                 weight_decay=0.0):
+    """`unroll` lower SGD steps, then one Adam step on lambda along the Neumann hypergradient
+    evaluated at the unrolled w (Sec. 3.3: the lower problem calls the upper one after its
+    unrolling steps; the best-response Jacobian is taken at the unrolled weights)."""
+    for _ in range(unroll):
+        w, mom = lower_sgd_step(prob, w, lam, mom, lr_w, mu, weight_decay)
+    dlam = hypergrad_neumann(prob, w, lam, K, alpha)
+    lam, am, av = adam_step(lam, dlam, am, av, t, lr_lam)
+    return w, mom, lam, am, av
+
+
+# ----------------------------------------------------------------------------
 # exact ridge lower solve (used to place w at w* for the ridge workload) and label noise
 # ----------------------------------------------------------------------------
 

@@ -80,12 +80,14 @@ def load_library():
     lib.betty_hypergrad_neumann.argtypes = [vp, f32p, f32p, C.c_int, C.c_float, f32p]
     lib.betty_hypergrad_fd.argtypes = [vp, f32p, f32p, C.c_int, C.c_float, C.c_float, f32p]
     lib.betty_hypergrad_cg.argtypes = [vp, f32p, f32p, C.c_int, f32p]
+    lib.betty_lower_sgd_step.argtypes = [vp, f32p, f32p, f32p, C.c_float, C.c_float, C.c_float, f32p]
+    lib.betty_upper_adam_step.argtypes = [vp, f32p, f32p, f32p, f32p, C.c_int, C.c_float, C.c_float, C.c_float, C.c_float]
     lib.betty_apply_label_noise.argtypes = [vp, vp, vp, vp, C.c_double, C.c_int, vp, vp]
     lib.betty_profile_enable.argtypes = [vp, C.c_int]
     lib.betty_profile_collect.argtypes = [vp]
     lib.betty_profile_get.argtypes = [vp, C.c_int, C.POINTER(ProfileRec)]
     for name in ("betty_lower_grad", "betty_upper_grad", "betty_hvp", "betty_mixed_vjp",
-                 "betty_hypergrad_neumann", "betty_hypergrad_fd", "betty_hypergrad_cg", "betty_apply_label_noise",
+                 "betty_hypergrad_neumann", "betty_hypergrad_fd", "betty_hypergrad_cg", "betty_lower_sgd_step", "betty_upper_adam_step", "betty_apply_label_noise",
                  "betty_profile_enable", "betty_profile_collect", "betty_profile_get"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -202,6 +204,21 @@ class Betty:
                                                 _ptr(lam, torch.float32, self.n_hyper), int(K),
                                                 _ptr(o, torch.float32, self.n_hyper)))
         return o
+
+    def betty_lower_sgd_step(self, w, lam, momentum, lr, mu, weight_decay=0.0, want_loss=False):
+        loss = self._vec(1) if want_loss else None
+        self._check(self.lib.betty_lower_sgd_step(self.h, _ptr(w, torch.float32, self.d),
+                                                  _ptr(lam, torch.float32, self.n_hyper),
+                                                  _ptr(momentum, torch.float32, self.d), float(lr), float(mu),
+                                                  float(weight_decay), _ptr(loss)))
+        return loss
+
+    def betty_upper_adam_step(self, lam, dlam, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8):
+        self._check(self.lib.betty_upper_adam_step(self.h, _ptr(lam, torch.float32, self.n_hyper),
+                                                   _ptr(dlam, torch.float32, self.n_hyper),
+                                                   _ptr(m, torch.float32, self.n_hyper),
+                                                   _ptr(v, torch.float32, self.n_hyper), int(t), float(lr),
+                                                   float(beta1), float(beta2), float(eps)))
 
     def betty_apply_label_noise(self, y, words, alt, p, want_mask=True):
         n = y.numel()

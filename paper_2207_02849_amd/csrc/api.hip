@@ -371,6 +371,7 @@ struct WgradSink {
   const float* x;
   float* v; float* p; float alpha;
   bool copies;              // also write the operand copies of the new v
+  float beta = 0.f, gamma = 0.f;   // EPI_WGRAD_SGD: momentum factor and plain weight decay
 };
 
 // All layers' parameter-shaped products in one launch: plain gradient a^T delta (rop = false) or
@@ -406,7 +407,7 @@ void wgrad_batch(betty_handle h, OperandSet& os, int side, bool rop, const Wgrad
       e.x = k.x ? k.x + li.w_off : nullptr;
       e.v = k.v ? k.v + li.w_off : nullptr;
       e.p = k.p ? k.p + li.w_off : nullptr;
-      e.alpha = k.alpha;
+      e.alpha = k.alpha; e.beta = k.beta; e.gamma = k.gamma;
       if (k.copies) {
         e.out = h->at<void>(os.Vn[l - 1]); e.ld = li.n_out_p;
         e.outT = h->at<void>(os.Vt[l - 1]); e.ldT = li.n_in_p;
@@ -421,7 +422,7 @@ void wgrad_batch(betty_handle h, OperandSet& os, int side, bool rop, const Wgrad
         j.x = k.x ? k.x + li.b_off : nullptr;
         j.v = k.v ? k.v + li.b_off : nullptr;
         j.p = k.p ? k.p + li.b_off : nullptr;
-        j.alpha = k.alpha;
+        j.alpha = k.alpha; j.beta = k.beta; j.gamma = k.gamma;
       }
     }
     double params = 0;
@@ -919,6 +920,53 @@ betty_status betty_hypergrad_cg(betty_handle h, const float* w, const float* lam
     else mixed_reweight_seq(h, os, lambda, q, 1.f, dlambda);
   };
   return run_cached(h, h->graph_cg, w, lambda, dlambda, K, 0.f, -1.f, body);
+}
+
+betty_status betty_lower_sgd_step(betty_handle h, float* w, const float* lambda, float* momentum, float lr, float mu,
+                                  float weight_decay, float* loss_or_null) {
+  CHECK(check_ready(h));
+  CHECK(check_vec(h, w, "w")); CHECK(check_vec(h, lambda, "lambda")); CHECK(check_vec(h, momentum, "momentum"));
+  if (loss_or_null) CHECK(check_vec(h, loss_or_null, "loss"));
+  if (!std::isfinite(lr) || !std::isfinite(mu) || !std::isfinite(weight_decay))
+    return fail(h, BETTY_EINVAL, "lr, mu and weight_decay must be finite");
+  if (overlaps(w, h->d * 4, momentum, h->d * 4) || overlaps(w, h->d * 4, lambda, h->n_hyper * 4) ||
+      overlaps(momentum, h->d * 4, lambda, h->n_hyper * 4))
+    return fail(h, BETTY_EINVAL, "w, momentum and lambda must not overlap");
+  OperandSet& os = h->sets[0];
+  const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
+  make_weight_operands(h, os, w);
+  forward_and_loss(h, os, SIDE_TRAIN, w, l2 ? nullptr : lambda);
+  backward_chain(h, os, SIDE_TRAIN);
+  if (loss_or_null) {                      // the cost at the w before the step
+    float* add = nullptr;
+    if (l2) {
+      add = h->f(h->scalars) + 8;
+      launch_l2_cost(h->ctx, lambda, w, h->d, h->at<double>(h->partials), add);
+    }
+    launch_weighted_loss_sum(h->ctx, h->f(os.side[0].s), h->f(os.side[0].ell), os.side[0].B, add, loss_or_null);
+  }
+  // momentum and parameters are updated in the epilogue of the weight-gradient launch
+  WgradSink k{EPI_WGRAD_SGD, nullptr, l2 ? lambda : nullptr, nullptr, momentum, w, lr, false};
+  k.beta = mu; k.gamma = weight_decay;
+  wgrad_batch(h, os, 0, false, k);
+  return finish(h);
+}
+
+betty_status betty_upper_adam_step(betty_handle h, float* lambda, const float* dlambda, float* m, float* v, int t,
+                                   float lr, float beta1, float beta2, float eps) {
+  if (!h) return BETTY_ENULL;
+  CHECK(check_vec(h, lambda, "lambda")); CHECK(check_vec(h, dlambda, "dlambda")); CHECK(check_vec(h, m, "m"));
+  CHECK(check_vec(h, v, "v"));
+  if (t < 1) return fail(h, BETTY_EINVAL, "t must be >= 1 (got %d)", t);
+  if (!std::isfinite(lr) || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f))
+    return fail(h, BETTY_EINVAL, "need finite lr, 0 <= beta1, beta2 < 1, eps >= 0");
+  const size_t nb = h->n_hyper * 4;
+  if (overlaps(lambda, nb, dlambda, nb) || overlaps(lambda, nb, m, nb) || overlaps(lambda, nb, v, nb) ||
+      overlaps(m, nb, v, nb) || overlaps(m, nb, dlambda, nb) || overlaps(v, nb, dlambda, nb))
+    return fail(h, BETTY_EINVAL, "lambda, dlambda, m and v must not overlap");
+  const float bias1 = 1.f - std::pow(beta1, (float)t), bias2 = 1.f - std::pow(beta2, (float)t);
+  launch_adam(h->ctx, lambda, dlambda, m, v, lr, beta1, beta2, eps, bias1, bias2, h->n_hyper);
+  return finish(h);
 }
 
 betty_status betty_apply_label_noise(betty_handle h, const int32_t* y, const uint32_t* words, const int32_t* alt,

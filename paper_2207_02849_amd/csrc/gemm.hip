@@ -129,6 +129,10 @@ __device__ __forceinline__ void epi_prefetch(const Epilogue& e, int M, int N, in
       R.b[k] = ok ? e.p[o] : 0.f;
       R.c[k] = ok ? e.lam[o] : 0.f;
       R.d[k] = ok ? e.x[o] : 0.f;
+    } else if constexpr (MODE == EPI_WGRAD_SGD) {
+      R.a[k] = ok ? e.v[o] : 0.f;
+      R.b[k] = ok ? e.p[o] : 0.f;
+      R.c[k] = (ok && e.lam) ? e.lam[o] : 0.f;
     }
   }
 }
@@ -207,6 +211,15 @@ __device__ __forceinline__ void epi_finish(const Epilogue& e, int M, int N, int 
 #pragma unroll
     for (int k = 0; k < 16; ++k)
       if (ok[k]) { e.v[of[k]] = val[k]; e.p[of[k]] = R.b[k] + val[k]; }
+  } else if constexpr (MODE == EPI_WGRAD_SGD) {          // lower optimiser step: momentum SGD in place
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      float gk = acc[k] + e.gamma * R.b[k];
+      if (e.lam) gk += 2.f * expf(R.c[k]) * R.b[k];
+      const float mk = e.beta * R.a[k] + gk;
+      if (ok[k]) { e.v[of[k]] = mk; e.p[of[k]] = R.b[k] - e.alpha * mk; }
+    }
+    return;
   } else if constexpr (MODE == EPI_WGRAD_NEUMANN_L2) {  // final step: only d(lambda) leaves the kernel
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
@@ -276,6 +289,15 @@ __device__ void bias_rows(const BiasJob& j, int row) {
       const float vn = vo - j.alpha * hv;
       j.v[row] = vn;
       j.p[row] += vn;
+      break;
+    }
+    case EPI_WGRAD_SGD: {
+      const float wo = j.p[row];
+      float gk = acc + j.gamma * wo;
+      if (j.lam) gk += 2.f * expf(j.lam[row]) * wo;
+      const float mk = j.beta * j.v[row] + gk;
+      j.v[row] = mk;
+      j.p[row] = wo - j.alpha * mk;
       break;
     }
     case EPI_WGRAD_NEUMANN_L2: {
@@ -505,7 +527,7 @@ static void launch_wgrad_mode(int mode, int total, hipStream_t st, const GemmBat
   switch (mode) {
 #define BETTY_CASE_W(M_) case M_: launch_one<T, BT, 4, 1, M_>(total, st, b, err); break;
     BETTY_CASE_W(EPI_WGRAD) BETTY_CASE_W(EPI_WGRAD_INIT) BETTY_CASE_W(EPI_WGRAD_NEUMANN)
-    BETTY_CASE_W(EPI_WGRAD_NEUMANN_L2)
+    BETTY_CASE_W(EPI_WGRAD_NEUMANN_L2) BETTY_CASE_W(EPI_WGRAD_SGD)
 #undef BETTY_CASE_W
     default: err = hipErrorInvalidValue; break;
   }

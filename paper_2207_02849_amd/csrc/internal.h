@@ -43,7 +43,8 @@ enum EpiMode {
   EPI_WGRAD,             // C = acc (+ 2 exp(lam) x)                       flat parameter layout
   EPI_WGRAD_INIT,        // v = p = acc; out = operand copies of v
   EPI_WGRAD_NEUMANN,     // Hv = acc (+ 2 exp(lam) v); v -= alpha Hv; p += v; out = copies of v
-  EPI_WGRAD_NEUMANN_L2   // last step for L2 decay: same update in registers, C = -2 exp(lam) x (alpha p)
+  EPI_WGRAD_NEUMANN_L2,  // last step for L2 decay: same update in registers, C = -2 exp(lam) x (alpha p)
+  EPI_WGRAD_SGD          // g = acc (+ 2 exp(lam) p) + gamma p; v <- beta v + g; p <- p - alpha v  (p = w, v = momentum)
 };
 
 struct Epilogue {
@@ -57,7 +58,7 @@ struct Epilogue {
   void* outT; int ldT;                   // operand-typed, transposed [col][row]
   float* C; long long ldc;               // fp32 row-major (flat parameter slice for the WGRAD modes)
   const float* lam; const float* x;      // same indexing as C
-  float* v; float* p; float alpha;
+  float* v; float* p; float alpha, beta, gamma;
 };
 
 struct GemmProblem { GemmArgs g; Epilogue e; };
@@ -65,7 +66,7 @@ struct GemmProblem { GemmArgs g; Epilogue e; };
 // out[row] from sum_k Mt[row][k]: bias-shaped slices of the WGRAD modes
 struct BiasJob {
   const void* Mt; int ld, rows, k, mode;
-  float* C; const float* lam; const float* x; float* v; float* p; float alpha;
+  float* C; const float* lam; const float* x; float* v; float* p; float alpha, beta, gamma;
 };
 
 constexpr int MAX_PROBLEMS = 8;
@@ -159,6 +160,8 @@ void launch_cg_step(Ctx&, float* q, float* r, const float* d, const float* Hd, c
 // d = r + (rs_new / rs) d   (beta = 0 if rs == 0)
 void launch_cg_dir(Ctx&, float* d, const float* r, const float* rs, const float* rs_new, size_t n);
 // c_i = (lp_i - lm_i) / (2 eps)   (0 if eps == 0)
+void launch_adam(Ctx&, float* x, const float* g, float* m, float* v, float lr, float beta1, float beta2, float eps,
+                 float bias1, float bias2, size_t n);
 void launch_fd_loss_diff(Ctx&, const float* lp, const float* lm, const float* eps_dev, int rows, float* c);
 void launch_l2_cost(Ctx&, const float* lam, const float* w, size_t n, double* partials, float* out_scalar);
 void launch_weighted_loss_sum(Ctx&, const float* s, const float* ell, int rows, const float* add_or_null, float* out);

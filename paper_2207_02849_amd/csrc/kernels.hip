@@ -423,6 +423,24 @@ void launch_cg_dir(Ctx& ctx, float* d, const float* r, const float* rs, const fl
   cg_dir_kernel<<<flat_grid(n), 256, 0, ctx.stream>>>(d, r, rs, rs_new, n);
 }
 
+// Adam on the upper parameters: bias1 = 1 - beta1^t, bias2 = 1 - beta2^t are formed on the host
+__global__ __launch_bounds__(256) void adam_kernel(float* x, const float* g, float* m, float* v, float lr, float beta1,
+                                                   float beta2, float eps, float bias1, float bias2, size_t n) {
+  FLAT_LOOP(i, n) {
+    const float gi = g[i];
+    const float mi = beta1 * m[i] + (1.f - beta1) * gi;
+    const float vi = beta2 * v[i] + (1.f - beta2) * gi * gi;
+    m[i] = mi;
+    v[i] = vi;
+    x[i] -= lr * (mi / bias1) / (sqrtf(vi / bias2) + eps);
+  }
+}
+void launch_adam(Ctx& ctx, float* x, const float* g, float* m, float* v, float lr, float beta1, float beta2, float eps,
+                 float bias1, float bias2, size_t n) {
+  Launch l(ctx, BETTY_K_VECTOR, 0, 28.0 * n);
+  adam_kernel<<<flat_grid(n), 256, 0, ctx.stream>>>(x, g, m, v, lr, beta1, beta2, eps, bias1, bias2, n);
+}
+
 __global__ __launch_bounds__(256) void fd_loss_diff_kernel(const float* lp, const float* lm, const float* eps_dev, int rows, float* c) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i >= rows) return;

@@ -280,3 +280,45 @@ def test_single_layer_softmax_regression():
     run_all(wl, big_alpha=0.3)
     wl = wk.tiny(kind="reweight", act="none", loss="ce", dims=(40, 6), batch=33, hidden=8)
     run_all(wl)
+
+
+@pytest.mark.parametrize("kind,prec,tol", [("l2", "fp32", 1e-4), ("reweight", "fp32", 1e-4), ("l2", "bf16", 2e-2)])
+def test_bilevel_steps_follow_the_oracle(kind, prec, tol):
+    """Unrolled lower SGD steps, Neumann hypergradient at the unrolled w, Adam step on lambda:
+    three outer steps of two inner steps each, every state vector against the oracle."""
+    wl = wk.tiny(kind=kind, act="gelu", dims=(60, 40, 10), batch=50, prec=prec, hidden=12)
+    prob = oracle_problem(wl)
+    b = binding.from_workload(wl)
+    w, lam = dev(wl.w), dev(wl.lam)
+    mom = torch.zeros_like(w)
+    am, av = torch.zeros_like(lam), torch.zeros_like(lam)
+    w64, lam64 = wl.w.astype(np.float64), wl.lam.astype(np.float64)
+    mom64, am64, av64 = np.zeros_like(w64), np.zeros_like(lam64), np.zeros_like(lam64)
+    lr_w, mu, wd, K, alpha, lr_lam = 0.05, 0.9, 1e-3, 3, 0.05, 0.01
+    for t in range(1, 4):
+        for _ in range(2):
+            loss = b.betty_lower_sgd_step(w, lam, mom, lr_w, mu, wd, want_loss=True)
+            ref_loss = orc.lower_cost(prob, w64, lam64)
+            w64, mom64 = orc.lower_sgd_step(prob, w64, lam64, mom64, lr_w, mu, wd)
+            assert abs(host(loss)[0] - ref_loss) < max(tol, 1e-5) * abs(ref_loss)
+        dlam = b.betty_hypergrad_neumann(w, lam, K, alpha)
+        b.betty_upper_adam_step(lam, dlam, am, av, t, lr_lam)
+        dlam64 = orc.hypergrad_neumann(prob, w64, lam64, K, alpha)
+        lam64, am64, av64 = orc.adam_step(lam64, dlam64, am64, av64, t, lr_lam)
+        assert rel_l2(host(w), w64) < tol, t
+        assert rel_l2(host(mom), mom64) < tol, t
+        assert rel_l2(host(dlam), dlam64) < tol, t
+        # Adam normalises the step (first step = lr * sign(g)), so lambda is compared on the scale of its
+        # change, and only with fp32 operands: a bf16 rounding that flips the sign of a tiny hypergradient
+        # entry moves that coordinate by 2 lr, which says nothing about parity
+        if prec == "fp32":
+            assert np.linalg.norm(host(lam) - lam64) < 2e-3 * np.linalg.norm(lam64 - wl.lam.astype(np.float64)), t
+        else:
+            lam = dev(lam64)          # keep both sides on the same trajectory
+    with pytest.raises(binding.BettyError) as e:
+        b.betty_upper_adam_step(lam, dlam, am, av, 0, lr_lam)
+    assert e.value.status == binding.EINVAL
+    with pytest.raises(binding.BettyError) as e:
+        b.betty_lower_sgd_step(w, lam, w, lr_w, mu)
+    assert e.value.status == binding.EINVAL
+    b.close()

@@ -525,3 +525,50 @@ def test_fd_product_keeps_reweighting_weights_frozen():
     assert rel_l2(orc.hvp_fd(prob, wl.w, wl.lam, v, 1e-4), Hv) < 1e-6
     got = orc.hypergrad_fd(prob, wl.w, wl.lam, 3, 0.05, 0.01)
     assert rel_l2(got, orc.hypergrad_neumann(prob, wl.w, wl.lam, 3, 0.05)) < 1e-3
+
+
+# ---------------------------------------------------------------- optimisation steps around the path
+
+def test_lower_sgd_reaches_the_ridge_minimiser_and_adam_first_step():
+    wl, prob, lam, w_star = ridge_setup()
+    w, mom = np.zeros_like(w_star), np.zeros_like(w_star)
+    for _ in range(400):
+        w, mom = orc.lower_sgd_step(prob, w, lam, mom, lr=0.1, mu=0.5)
+    assert rel_l2(w, w_star) < 1e-10
+    # mu = 0, no decay: plain gradient descent
+    w1, m1 = orc.lower_sgd_step(prob, w_star + 1.0, lam, np.zeros_like(w_star), lr=0.05, mu=0.0)
+    assert rel_l2(w1, (w_star + 1.0) - 0.05 * orc.lower_grad(prob, w_star + 1.0, lam)[1]) < 1e-15
+    # weight decay adds wd * w to the gradient
+    w2, _ = orc.lower_sgd_step(prob, w_star + 1.0, lam, np.zeros_like(w_star), lr=0.05, mu=0.0, weight_decay=0.3)
+    assert rel_l2(w1 - w2, 0.05 * 0.3 * (w_star + 1.0)) < 1e-12
+    # first Adam step moves every coordinate by lr * sign(g) (bias-corrected moments cancel)
+    g = _vec(21, 10)
+    x, m, v = orc.adam_step(np.zeros(10), g, np.zeros(10), np.zeros(10), 1, lr=0.01, eps=0.0)
+    assert np.allclose(x, -0.01 * np.sign(g), atol=1e-15)
+    # against torch.optim.Adam over three steps
+    xt = torch.zeros(10, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.Adam([xt], lr=0.01)
+    x, m, v = np.zeros(10), np.zeros(10), np.zeros(10)
+    for t in range(1, 4):
+        gt = _vec(30 + t, 10)
+        xt.grad = torch.tensor(gt)
+        opt.step()
+        x, m, v = orc.adam_step(x, gt, m, v, t, lr=0.01)
+        assert np.allclose(x, xt.detach().numpy(), atol=1e-14)
+
+
+def test_bilevel_steps_lower_the_validation_loss_on_ridge():
+    """Driving lambda with the hypergradient must reduce L_val(w*(lambda))."""
+    wl, prob, lam, w_star = ridge_setup()
+    Xv, tv = wl.X_val.astype(np.float64), wl.t_val.astype(np.float64).ravel()
+
+    def val_at(l):
+        ws = orc.ridge_solve(wl.X_tr, wl.t_tr, l)
+        return ((Xv @ ws - tv) ** 2).mean()
+    w, mom = w_star.copy(), np.zeros_like(w_star)
+    am, av = np.zeros_like(lam), np.zeros_like(lam)
+    before = val_at(lam)
+    for t in range(1, 31):
+        w, mom, lam, am, av = orc.bilevel_step(prob, w, mom, lam, am, av, t, unroll=20, lr_w=0.1, mu=0.5,
+                                               K=40, alpha=0.2, lr_lam=0.05)
+    assert val_at(lam) < before
