@@ -435,17 +435,21 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
 
   if (tb < te) BETTY_GLOAD(ra0, rb0, tb)
   if (tb + 1 < te) BETTY_GLOAD(ra1, rb1, tb + 1)
-  // steady state while both refills of an iteration stay inside this group's k-range
+  // Unsplit launches (KG == 1) have long k loops: steady state while both refills of an iteration
+  // stay inside the k-range, then a short tail.  K-split launches run a handful of tiles per
+  // group; they keep the compact loop (less code to fetch for a kernel that lives a few us).
   const int n_full = te - tb;                       // tiles this group really has (<= NI)
   int it = 0;
-  if (n_full > 3) {                                 // first pair peeled: no barrier before the first store
-    BETTY_STAGE(ra0, rb0, tb, true, true)
-    BETTY_STAGE(ra1, rb1, tb + 1, false, true)
-    it = 2;
-  }
-  for (; it + 3 < n_full; it += 2) {
-    BETTY_STAGE(ra0, rb0, tb + it, false, true)
-    BETTY_STAGE(ra1, rb1, tb + it + 1, false, true)
+  if constexpr (KG == 1) {
+    if (n_full > 3) {                               // first pair peeled: no barrier before the first store
+      BETTY_STAGE(ra0, rb0, tb, true, true)
+      BETTY_STAGE(ra1, rb1, tb + 1, false, true)
+      it = 2;
+    }
+    for (; it + 3 < n_full; it += 2) {
+      BETTY_STAGE(ra0, rb0, tb + it, false, true)
+      BETTY_STAGE(ra1, rb1, tb + it + 1, false, true)
+    }
   }
   for (; it < NI; it += 2) {
     BETTY_STAGE(ra0, rb0, tb + it, it == 0, false)
