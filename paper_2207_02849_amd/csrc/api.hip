@@ -195,7 +195,7 @@ int plan_chain(betty_handle h, Elem elem, int tiles128, int Ktot_p) {
   if (tiles128 >= h->tune_tile128_min) return GEMM_128x1;
   if (tiles128 >= h->tune_tile128_min / 2 && TT >= 8) return GEMM_128x2;
   const int tiles64 = 4 * tiles128;
-  if (tiles64 < h->tune_target_blocks / 2 && TT >= 16) return GEMM_32x16;
+  if (tiles64 < h->tune_target_blocks / 2 && TT >= 16) return GEMM_32x8;
   if (tiles64 < h->tune_target_blocks && TT >= 8) return GEMM_64x4;
   return GEMM_64x1;
 }

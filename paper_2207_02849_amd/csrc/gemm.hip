@@ -330,7 +330,11 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
   const int kg = __builtin_amdgcn_readfirstlane(threadIdx.x / GT);
   const int tid = threadIdx.x % GT, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = WPG == 4 ? wave >> 1 : 0, wn = WPG == 4 ? wave & 1 : 0;
-  u32x4* sA = smem + kg * ((BM + BN) * ROW);
+  // Unsplit launches keep two LDS operand buffers and alternate between them, so the stores of
+  // one k-tile overlap the multiplication of the previous one and a k-tile costs one barrier.
+  constexpr bool DB = KG == 1;
+  constexpr int LBUF = (BM + BN) * ROW;            // one operand buffer, in chunks
+  u32x4* sA = smem + kg * LBUF;
   u32x4* sB = sA + BM * ROW;
   // a one-wavefront group owns its LDS region alone: no workgroup barrier inside the k loop
 #define BETTY_GROUP_SYNC() do { if constexpr (WPG == 1) __builtin_amdgcn_wave_barrier(); else __syncthreads(); } while (0)
@@ -402,18 +406,20 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
   // In the steady-state loop the refill is unconditional (always_), so the loop body has no branch
   // around memory instructions: the compiler then knows exactly how many loads are in flight and
   // waits only for the register set it is about to store.  The last stages refill conditionally.
-#define BETTY_STAGE(RA_, RB_, t_, first_, always_)                                                   \
+#define BETTY_STAGE(RA_, RB_, t_, first_, always_, buf_)                                                   \
   {                                                                                                  \
     const bool live_ = KG == 1 || (t_) < te;                                                         \
-    if (!(first_)) BETTY_GROUP_SYNC();                                                               \
+    u32x4* const sA_ = sA + (DB ? (buf_) * LBUF : 0);                                                \
+    u32x4* const sB_ = sB + (DB ? (buf_) * LBUF : 0);                                                \
+    if (!DB && !(first_)) BETTY_GROUP_SYNC();                                                        \
     if (live_) {                                                                                     \
       _Pragma("unroll") for (int i_ = 0; i_ < LA; ++i_) {                                            \
         const int idx_ = tid + i_ * GT;                                                              \
-        sA[(idx_ / NCH) * ROW + idx_ % NCH] = RA_[i_];                                               \
+        sA_[(idx_ / NCH) * ROW + idx_ % NCH] = RA_[i_];                                              \
       }                                                                                              \
       _Pragma("unroll") for (int i_ = 0; i_ < LB; ++i_) {                                            \
         const int idx_ = tid + i_ * GT;                                                              \
-        sB[(idx_ / NCH) * ROW + idx_ % NCH] = RB_[i_];                                               \
+        sB_[(idx_ / NCH) * ROW + idx_ % NCH] = RB_[i_];                                              \
       }                                                                                              \
     }                                                                                                \
     BETTY_GROUP_SYNC();                                                                              \
@@ -423,9 +429,9 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
         const int c_ = 2 * j_ + (lane >> 5);                                                         \
         u32x4 af_[TM], bf_[TN];                                                                      \
         _Pragma("unroll") for (int i_ = 0; i_ < TM; ++i_)                                            \
-          af_[i_] = sA[(wm * TM * 32 + i_ * 32 + (lane & 31)) * ROW + c_];                           \
+          af_[i_] = sA_[(wm * TM * 32 + i_ * 32 + (lane & 31)) * ROW + c_];                          \
         _Pragma("unroll") for (int i_ = 0; i_ < TN; ++i_)                                            \
-          bf_[i_] = sB[(wn * TN * 32 + i_ * 32 + (lane & 31)) * ROW + c_];                           \
+          bf_[i_] = sB_[(wn * TN * 32 + i_ * 32 + (lane & 31)) * ROW + c_];                          \
         _Pragma("unroll") for (int i_ = 0; i_ < TM; ++i_)                                            \
           _Pragma("unroll") for (int jn_ = 0; jn_ < TN; ++jn_)                                       \
             MfmaChunk<T>::run(af_[i_], bf_[jn_], acc[i_ * TN + jn_]);                                \
@@ -442,18 +448,18 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
   int it = 0;
   if constexpr (KG == 1) {
     if (n_full > 3) {                               // first pair peeled: no barrier before the first store
-      BETTY_STAGE(ra0, rb0, tb, true, true)
-      BETTY_STAGE(ra1, rb1, tb + 1, false, true)
+      BETTY_STAGE(ra0, rb0, tb, true, true, 0)
+      BETTY_STAGE(ra1, rb1, tb + 1, false, true, 1)
       it = 2;
     }
     for (; it + 3 < n_full; it += 2) {
-      BETTY_STAGE(ra0, rb0, tb + it, false, true)
-      BETTY_STAGE(ra1, rb1, tb + it + 1, false, true)
+      BETTY_STAGE(ra0, rb0, tb + it, false, true, 0)
+      BETTY_STAGE(ra1, rb1, tb + it + 1, false, true, 1)
     }
   }
   for (; it < NI; it += 2) {
-    BETTY_STAGE(ra0, rb0, tb + it, it == 0, false)
-    if (it + 1 < NI) BETTY_STAGE(ra1, rb1, tb + it + 1, false, false)
+    BETTY_STAGE(ra0, rb0, tb + it, it == 0, false, 0)
+    if (it + 1 < NI) BETTY_STAGE(ra1, rb1, tb + it + 1, false, false, 1)
   }
 #undef BETTY_STAGE
 #undef BETTY_GLOAD
@@ -496,7 +502,7 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
 
 template <typename T, int BT, int WPG, int KG>
 constexpr size_t lds_bytes() {
-  constexpr size_t operands = (size_t)KG * 2 * BT * (GEMM_NCH + 1) * 16;
+  constexpr size_t operands = (size_t)(KG == 1 ? 2 : KG) * 2 * BT * (GEMM_NCH + 1) * 16;
   constexpr size_t reduce = (size_t)(KG - 1) * BT * BT * 4;
   return operands > reduce ? operands : reduce;
 }
@@ -551,14 +557,14 @@ static void launch_elem(int cfg, int mode, int total, hipStream_t st, const Gemm
     case GEMM_128x2: launch_chain_mode<T, 128, 4, 2>(mode, total, st, b, err); break;
     case GEMM_64x1: launch_chain_mode<T, 64, 4, 1>(mode, total, st, b, err); break;
     case GEMM_64x4: launch_chain_mode<T, 64, 4, 4>(mode, total, st, b, err); break;
-    case GEMM_32x16: launch_chain_mode<T, 32, 1, 16>(mode, total, st, b, err); break;
+    case GEMM_32x8: launch_chain_mode<T, 32, 1, 8>(mode, total, st, b, err); break;
     default: err = hipErrorInvalidValue; break;
   }
 }
 
 int gemm_ktile_elems(Elem elem) { return GEMM_NCH * (elem == ELEM_BF16 ? 8 : 4); }
-int gemm_cfg_tile(int cfg) { return (cfg == GEMM_128x1 || cfg == GEMM_128x2) ? 128 : cfg == GEMM_32x16 ? 32 : 64; }
-static int gemm_cfg_waves(int cfg) { return cfg == GEMM_128x2 ? 8 : cfg == GEMM_64x4 ? 16 : cfg == GEMM_32x16 ? 16 : 4; }
+int gemm_cfg_tile(int cfg) { return (cfg == GEMM_128x1 || cfg == GEMM_128x2) ? 128 : cfg == GEMM_32x8 ? 32 : 64; }
+static int gemm_cfg_waves(int cfg) { return cfg == GEMM_128x2 ? 8 : cfg == GEMM_64x4 ? 16 : cfg == GEMM_32x8 ? 8 : 4; }
 
 void launch_gemm_batch(Ctx& ctx, Elem elem, int cfg, GemmBatch& b, double flops, double bytes) {
   const int bt = gemm_cfg_tile(cfg);
