@@ -35,7 +35,17 @@ Lower costs:
               sigmoid out) fed the *value* of l_i, i.e. treated as constant
               when differentiating in w (App. B Listing 3: the reweighting
               input is detached; App. C: 1-100-1 weight net)
+  "proximal": L_L = (1/B) sum_i l_i(w) + sum_j rho_j (w_j - a_j)^2, the finetuning level of the
+              three-level program of Sec. 4.3: its "hyperparameter" a is the optimum of the level
+              below it in the chain (the pretraining weights).  rho_j = rho on every parameter,
+              or 0 on the last layer's when prox_skip_last (App. B Listing 5 leaves the
+              classifier head out of the proximal term).
 Upper cost:   L_U = mean_i l_i(w) on the validation batch (Listing 3, level 2).
+
+Three levels (Sec. 3.1 Eq. 2, Sec. 4.3): with theta -> w*(theta) -> v*(w*) -> L_U(v*) the
+single path gives  dL_U/dtheta = (dw*/dtheta) (dv*/dw*) grad_v L_U, evaluated from the right:
+each factor applied to a vector is the same base operation (Eq. 3-4) on one of the two lower
+problems, `best_response_neumann`.
 
 Parity status of each function against pins other than itself is listed in
 tests/test_oracle_pins.py; no function here is "parity unpinned".
@@ -56,7 +66,7 @@ class Problem:
     dims: tuple
     act: str                 # "none" | "relu" | "gelu"
     loss: str                # "mse" | "ce"
-    hp: str                  # "l2" | "reweight"
+    hp: str                  # "l2" | "reweight" | "proximal"
     has_bias: bool
     X_tr: np.ndarray
     X_val: np.ndarray
@@ -65,6 +75,8 @@ class Problem:
     t_tr: Optional[np.ndarray] = None    # real targets (mse), (B, n_L)
     t_val: Optional[np.ndarray] = None
     wnet_hidden: int = 100
+    prox_rho: float = 0.0                # "proximal": coefficient of ||w - a||^2
+    prox_skip_last: bool = False         # "proximal": no proximal term on the last layer
 
     def __post_init__(self):
         self.X_tr = np.asarray(self.X_tr, dtype=F64)
@@ -256,6 +268,15 @@ def data_cost_and_grad(prob: Problem, w, lam, which, ell_frozen=None):
     return cost, grad
 
 
+def prox_coeff(prob: Problem):
+    """rho_j of the proximal cost, one entry per parameter (weights and biases alike)."""
+    c = np.full(prob.d, float(prob.prox_rho), dtype=F64)
+    if prob.prox_skip_last:
+        n_in, n_out = prob.dims[-2], prob.dims[-1]
+        c[prob.d - (n_in * n_out + (n_out if prob.has_bias else 0)):] = 0.0
+    return c
+
+
 def lower_cost(prob: Problem, w, lam):
     """L_L(w, lambda): the training cost whose argmin defines w*(lambda) (Eq. 4)."""
     w = np.asarray(w, dtype=F64)
@@ -266,6 +287,9 @@ def lower_cost(prob: Problem, w, lam):
     cost = float((s * ell).sum())
     if prob.hp == "l2":
         cost += float((np.exp(np.asarray(lam, dtype=F64)) * w * w).sum())
+    if prob.hp == "proximal":
+        diff = w - np.asarray(lam, dtype=F64)
+        cost += float((prox_coeff(prob) * diff * diff).sum())
     return cost
 
 
@@ -280,6 +304,11 @@ def lower_grad(prob: Problem, w, lam, ell_frozen=None):
         e = np.exp(np.asarray(lam, dtype=F64))
         cost += float((e * w * w).sum())
         grad = grad + 2.0 * e * w
+    if prob.hp == "proximal":
+        c = prox_coeff(prob)
+        diff = w - np.asarray(lam, dtype=F64)
+        cost += float((c * diff * diff).sum())
+        grad = grad + 2.0 * c * diff
     return cost, grad
 
 
@@ -338,6 +367,8 @@ def hvp(prob: Problem, w, lam, v):
     Hv = join_params(prob, out)
     if prob.hp == "l2":
         Hv = Hv + 2.0 * np.exp(np.asarray(lam, dtype=F64)) * v
+    if prob.hp == "proximal":
+        Hv = Hv + 2.0 * prox_coeff(prob) * v
     return Hv
 
 
@@ -386,6 +417,9 @@ def mixed_vjp(prob: Problem, w, lam, q):
     lam = np.asarray(lam, dtype=F64)
     if prob.hp == "l2":
         return -2.0 * np.exp(lam) * w * q
+    if prob.hp == "proximal":
+        # d/da of <2 rho (w - a), q> is -2 rho q
+        return 2.0 * prox_coeff(prob) * q
     c, ell = per_sample_directional(prob, w, q)
     B = ell.shape[0]
     return -weight_net_theta_vjp(ell, lam, prob.wnet_hidden, c) / B
@@ -397,6 +431,8 @@ def lambda_grad(prob: Problem, w, lam, ell_frozen=None):
     lam = np.asarray(lam, dtype=F64)
     if prob.hp == "l2":
         return np.exp(lam) * w * w
+    if prob.hp == "proximal":
+        return -2.0 * prox_coeff(prob) * (w - lam)
     X, target = prob.batch("train")
     _, zs = forward(prob, w, X)
     ell, _ = sample_losses(prob, zs[-1], target)
@@ -445,6 +481,25 @@ def hypergrad_neumann(prob: Problem, w, lam, K, alpha):
     g = upper_grad(prob, w)[1]
     q = neumann_q(prob, w, lam, g, K, alpha, lambda v: hvp(prob, w, lam, v))
     return mixed_vjp(prob, w, lam, q)
+
+
+def best_response_neumann(prob: Problem, w, lam, u, K, alpha):
+    """The base operation of Sec. 3.2 (Eq. 3-4): (dw*/dlambda) applied to a vector u of the size
+    of w, i.e. -(d^2 L_L/dlambda dw) H^{-1} u with the K-step Neumann approximation of H^{-1} u.
+    `hypergrad_neumann` is this with u = grad_w L_U."""
+    q = neumann_q(prob, w, lam, np.asarray(u, dtype=F64), K, alpha, lambda v: hvp(prob, w, lam, v))
+    return mixed_vjp(prob, w, lam, q)
+
+
+def hypergrad_chain3(pre: Problem, ft: Problem, w, theta, v, K_pre, alpha_pre, K_ft, alpha_ft):
+    """dL_U/dtheta of the three-level chain theta -> w*(theta) -> v*(w*) -> L_U(v*) (Eq. 2 with
+    its single path; Sec. 4.3), from the right:  u = (dv*/dw) grad_v L_U  on the finetuning
+    problem `ft` (proximal cost anchored at w, parameters v, upper cost on ft's validation batch),
+    then (dw*/dtheta) u on the pretraining problem `pre` (parameters w, hyperparameters theta)."""
+    assert ft.hp == "proximal" and ft.d == pre.d
+    g = upper_grad(ft, v)[1]
+    u = best_response_neumann(ft, v, w, g, K_ft, alpha_ft)
+    return best_response_neumann(pre, w, theta, u, K_pre, alpha_pre)
 
 
 def hypergrad_fd(prob: Problem, w, lam, K, alpha, eps_scale):

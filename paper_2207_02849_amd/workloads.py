@@ -31,7 +31,8 @@ class Workload:
     dims: tuple            # (n_0, ..., n_L): L linear layers
     act: str               # "none" | "relu" | "gelu"
     loss: str              # "mse" | "ce"
-    hp: str                # "l2" (lambda has length d) | "reweight" (1-H-1 weight net)
+    hp: str                # "l2" (lambda has length d) | "reweight" (1-H-1 weight net) |
+                           # "proximal" (lambda = anchor parameters, length d)
     prec: str              # "fp32" | "bf16"
     has_bias: bool
     K: int
@@ -51,6 +52,8 @@ class Workload:
     noise_words: Optional[np.ndarray] = None   # uint32, one per train sample
     noise_alt: Optional[np.ndarray] = None     # int32 replacement class per sample
     noise_p: float = 0.0
+    prox_rho: float = 0.0                 # "proximal": coefficient of the squared distance to the anchor
+    prox_skip_last: bool = False          # "proximal": last layer left out of the proximal term
     extra: dict = field(default_factory=dict)
 
     @property
@@ -186,7 +189,7 @@ def config(index: int, seed: int = 0) -> Workload:
 
 
 def tiny(kind="l2", act="gelu", seed=0, dims=(5, 4, 3, 3), batch=7, has_bias=True,
-         loss="ce", noise_p=0.3, hidden=6, prec="fp32"):
+         loss="ce", noise_p=0.3, hidden=6, prec="fp32", prox_rho=0.05, prox_skip_last=False):
     """Small ragged problems for unit tests (odd sizes on purpose)."""
     rng = _rng(seed + 1000)
     C = dims[-1]
@@ -207,9 +210,53 @@ def tiny(kind="l2", act="gelu", seed=0, dims=(5, 4, 3, 3), batch=7, has_bias=Tru
     w = np.concatenate(parts).astype(np.float32)
     if kind == "l2":
         lam = (math.log(0.05) + 0.3 * rng.standard_normal(w.size)).astype(np.float32)
+    elif kind == "proximal":
+        lam = (w + 0.2 * rng.standard_normal(w.size)).astype(np.float32)     # the anchor
     else:
         lam = _init_wnet(rng, hidden)
     return Workload(name=f"tiny_{kind}_{act}_{loss}", dims=tuple(dims), act=act, loss=loss,
                     hp=kind, prec=prec, has_bias=has_bias, K=3, alpha=0.05, eps_scale=0.01,
                     X_tr=X_tr, X_val=X_val, y_tr=y_tr, y_val=y_val, t_tr=t_tr, t_val=t_val,
-                    w=w, lam=lam, wnet_hidden=hidden)
+                    w=w, lam=lam, wnet_hidden=hidden, prox_rho=prox_rho,
+                    prox_skip_last=prox_skip_last)
+
+
+def chain3(seed=0, dims=(6, 5, 4), act="gelu", prec="fp32", batch=9, has_bias=True, hidden=6,
+           noise_p=0.3, rho=0.05, skip_last=True, K=3, alpha=0.05, sigma=1.0, name="chain3"):
+    """The two lower problems of the three-level program of Sec. 4.3 on one MLP architecture.
+
+    Returns (pre, ft).  `pre` is a reweighting problem on "source-domain" data (its own mixture,
+    noisy labels); its parameters `pre.w` are the pretraining weights and `pre.lam` the weight-net
+    parameters theta.  `ft` is the finetuning problem on "target-domain" data (the source class
+    means shifted by a random offset), with the proximal cost anchored at the pretraining weights:
+    `ft.lam` is `pre.w`, `ft.w` the finetuned parameters v; ft's validation batch carries the
+    top-level cost.
+    """
+    rng = _rng(seed + 77000)
+    C = dims[-1]
+    means = rng.standard_normal((C, dims[0]))
+    shift = 0.5 * rng.standard_normal((C, dims[0]))
+
+    def draw(m, b):
+        y = rng.integers(0, C, size=b, dtype=np.int64)
+        x = m[y] + sigma * rng.standard_normal((b, dims[0]))
+        return x.astype(np.float32), y.astype(np.int32)
+
+    Xs, ys_clean = draw(means, batch)
+    Xs_val, ys_val = draw(means, batch)               # unused by the chain; fills pre's validation slot
+    Xt, yt = draw(means + shift, batch + 1)
+    Xt_val, yt_val = draw(means + shift, batch + 3)
+    words = rng.integers(0, 2 ** 32, size=batch, dtype=np.uint64).astype(np.uint32)
+    alt = rng.integers(0, C, size=batch, dtype=np.int64).astype(np.int32)
+    ys = np.where(words.astype(np.uint64) < noise_threshold(noise_p), alt, ys_clean).astype(np.int32)
+    w = _init_mlp(rng, dims, has_bias)
+    v = (w + 0.1 * _init_mlp(rng, dims, has_bias)).astype(np.float32)
+    theta = _init_wnet(rng, hidden)
+    pre = Workload(name=name + "_pretrain", dims=tuple(dims), act=act, loss="ce", hp="reweight", prec=prec,
+                   has_bias=has_bias, K=K, alpha=alpha, eps_scale=0.01, X_tr=Xs, X_val=Xs_val, y_tr=ys,
+                   y_val=ys_val, w=w, lam=theta, wnet_hidden=hidden, y_clean=ys_clean, noise_words=words,
+                   noise_alt=alt, noise_p=noise_p)
+    ft = Workload(name=name + "_finetune", dims=tuple(dims), act=act, loss="ce", hp="proximal", prec=prec,
+                  has_bias=has_bias, K=K, alpha=alpha, eps_scale=0.01, X_tr=Xt, X_val=Xt_val, y_tr=yt,
+                  y_val=yt_val, w=v, lam=w.copy(), prox_rho=rho, prox_skip_last=skip_last)
+    return pre, ft

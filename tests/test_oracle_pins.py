@@ -68,6 +68,16 @@ def torch_costs(wl):
         loss = per_sample(w, Xtr, wl.y_tr, wl.t_tr)
         if wl.hp == "l2":
             return loss.mean() + (torch.exp(lam) * w * w).sum()
+        if wl.hp == "proximal":
+            # the finetuning cost of Sec. 4.3: squared distance to the anchor, the last layer's
+            # parameters left out when prox_skip_last (written tensor by tensor, as in Listing 5)
+            total, o, L = loss.mean(), 0, len(dims) - 1
+            for l in range(L):
+                n = dims[l] * dims[l + 1] + (dims[l + 1] if wl.has_bias else 0)
+                coef = 0.0 if (wl.prox_skip_last and l == L - 1) else wl.prox_rho
+                total = total + coef * ((w[o:o + n] - lam[o:o + n]) ** 2).sum()
+                o += n
+            return total
         H = wl.wnet_hidden
         u1, b1, u2, b2 = lam[:H], lam[H:2 * H], lam[2 * H:3 * H], lam[3 * H]
         x = loss.detach().reshape(-1, 1)
@@ -88,6 +98,9 @@ TINY = [
     dict(kind="l2", act="gelu", loss="mse", dims=(4, 5, 2)),
     dict(kind="reweight", act="gelu", loss="ce"),
     dict(kind="reweight", act="relu", loss="ce", dims=(6, 5, 4), batch=9),
+    dict(kind="proximal", act="gelu", loss="ce", prox_rho=0.3),
+    dict(kind="proximal", act="relu", loss="ce", dims=(6, 5, 4), batch=9, prox_rho=0.1, prox_skip_last=True),
+    dict(kind="proximal", act="none", loss="mse", dims=(5, 3), has_bias=False, prox_rho=0.2),
 ]
 
 
@@ -355,6 +368,8 @@ def test_mixed_vjp_vs_torch_and_fd(cfg):
     assert rel_l2(orc.mixed_vjp_fd(prob, wl.w, wl.lam, q, 0.01 if wl.act != "relu" else 1e-6), got) < 1e-3
     if wl.hp == "l2":
         assert rel_l2(got, -2 * np.exp(lam0) * wl.w.astype(np.float64) * q) < 1e-15
+    if wl.hp == "proximal" and not wl.prox_skip_last:
+        assert rel_l2(got, 2 * wl.prox_rho * q) < 1e-15
 
 
 def test_per_sample_directional_vs_fd():
@@ -572,3 +587,126 @@ def test_bilevel_steps_lower_the_validation_loss_on_ridge():
         w, mom, lam, am, av = orc.bilevel_step(prob, w, mom, lam, am, av, t, unroll=20, lr_w=0.1, mu=0.5,
                                                K=40, alpha=0.2, lr_lam=0.05)
     assert val_at(lam) < before
+
+
+# ---------------------------------------------------------------- three-level chain (Sec. 3.1 Eq. 2, Sec. 4.3)
+
+def test_proximal_best_response_closed_form_on_least_squares():
+    """Linear least squares + rho ||v - a||^2 has v*(a) = (X'X/n + rho I)^-1 (X't/n + rho a), so
+    dv*/da = rho (X'X/n + rho I)^-1 (symmetric) and (dv*/da) u is a dense solve; the converged
+    Neumann series must reproduce it, and a finite difference through the exact solver too."""
+    wl = wk.tiny(kind="proximal", act="none", loss="mse", dims=(6, 1), has_bias=False, batch=12, prox_rho=0.4)
+    prob = oracle_problem(wl)
+    X = wl.X_tr.astype(np.float64)
+    t = wl.t_tr.astype(np.float64).ravel()
+    n, rho = X.shape[0], wl.prox_rho
+    a = wl.lam.astype(np.float64)
+    A = X.T @ X / n + rho * np.eye(6)
+
+    def solve(anchor):
+        return np.linalg.solve(A, X.T @ t / n + rho * anchor)
+
+    v_star = solve(a)
+    assert np.linalg.norm(orc.lower_grad(prob, v_star, a)[1]) < 1e-12
+    u = _vec(21, 6)
+    expect = rho * np.linalg.solve(A, u)
+    H = 2.0 * A
+    alpha = 1.0 / np.linalg.eigvalsh(H).max()
+    K = int(math.ceil(40.0 / (alpha * np.linalg.eigvalsh(H).min())))
+    got = orc.best_response_neumann(prob, v_star, a, u, K, alpha)
+    assert rel_l2(got, expect) < 1e-10
+    # finite differences through the exact solver: column j of dv*/da
+    h = 1e-6
+    J = np.zeros((6, 6))
+    for j in range(6):
+        e = np.zeros(6)
+        e[j] = h
+        J[:, j] = (solve(a + e) - solve(a - e)) / (2 * h)
+    assert rel_l2(got, J.T @ u) < 1e-8
+    # with u the validation gradient this is the two-level hypergradient of the same problem
+    g = orc.upper_grad(prob, v_star)[1]
+    assert rel_l2(orc.hypergrad_neumann(prob, v_star, a, K, alpha),
+                  orc.best_response_neumann(prob, v_star, a, g, K, alpha)) < 1e-14
+
+
+def test_chain3_total_derivative_through_nested_exact_solvers():
+    """All-quadratic three-level program: ridge pretraining w*(theta) with per-parameter decay
+    exp(theta), proximal least-squares finetuning v*(w*), MSE validation cost.  Both argmins have
+    closed forms, so dL/dtheta is pinned by central differences through the nested solvers."""
+    rng = np.random.default_rng(5)
+    nf = 7
+    Xs, ts = rng.standard_normal((20, nf)), rng.standard_normal(20)
+    Xt, tt = rng.standard_normal((15, nf)), rng.standard_normal(15)
+    Xv, tv = rng.standard_normal((11, nf)), rng.standard_normal(11)
+    theta = math.log(0.3) + 0.2 * rng.standard_normal(nf)
+    rho = 0.25
+    pre = orc.Problem(dims=(nf, 1), act="none", loss="mse", hp="l2", has_bias=False, X_tr=Xs, X_val=Xs,
+                      t_tr=ts.reshape(-1, 1), t_val=ts.reshape(-1, 1))
+    ft = orc.Problem(dims=(nf, 1), act="none", loss="mse", hp="proximal", has_bias=False, X_tr=Xt, X_val=Xv,
+                     t_tr=tt.reshape(-1, 1), t_val=tv.reshape(-1, 1), prox_rho=rho)
+
+    def w_of(th):
+        return np.linalg.solve(Xs.T @ Xs / 20 + np.diag(np.exp(th)), Xs.T @ ts / 20)
+
+    def v_of(w):
+        return np.linalg.solve(Xt.T @ Xt / 15 + rho * np.eye(nf), Xt.T @ tt / 15 + rho * w)
+
+    def top(th):
+        r = Xv @ v_of(w_of(th)) - tv
+        return float(r @ r) / 11
+
+    h = 1e-6
+    fd = np.zeros(nf)
+    for j in range(nf):
+        e = np.zeros(nf)
+        e[j] = h
+        fd[j] = (top(theta + e) - top(theta - e)) / (2 * h)
+    w = w_of(theta)
+    v = v_of(w)
+    H1 = 2.0 * (Xs.T @ Xs / 20 + np.diag(np.exp(theta)))
+    H2 = 2.0 * (Xt.T @ Xt / 15 + rho * np.eye(nf))
+    a1, a2 = 1.0 / np.linalg.eigvalsh(H1).max(), 1.0 / np.linalg.eigvalsh(H2).max()
+    K1 = int(math.ceil(40.0 / (a1 * np.linalg.eigvalsh(H1).min())))
+    K2 = int(math.ceil(40.0 / (a2 * np.linalg.eigvalsh(H2).min())))
+    got = orc.hypergrad_chain3(pre, ft, w, theta, v, K1, a1, K2, a2)
+    assert rel_l2(got, fd) < 1e-7
+
+
+@pytest.mark.parametrize("act,skip", [("gelu", True), ("relu", False)])
+def test_chain3_truncated_series_against_dense_autograd_matrices(act, skip):
+    """General MLPs, any K: both truncated series written with dense Hessians and mixed partials
+    from torch's fp64 autograd on forward-only statements of the two lower costs."""
+    pre_wl, ft_wl = wk.chain3(seed=3, act=act, skip_last=skip)
+    pre, ft = oracle_problem(pre_wl), oracle_problem(ft_wl)
+    w, v, theta = (x.astype(np.float64) for x in (pre_wl.w, ft_wl.w, pre_wl.lam))
+    d = w.size
+
+    def dense(wl, params, hyper):
+        lower, upper = torch_costs(wl)
+        pt = torch.tensor(params, requires_grad=True)
+        ht = torch.tensor(hyper, requires_grad=True)
+        g, = torch.autograd.grad(lower(pt, ht), pt, create_graph=True)
+        Hr, Mr = [], []
+        for j in range(d):
+            hw, hl = torch.autograd.grad(g[j], (pt, ht), retain_graph=True)
+            Hr.append(hw.numpy())
+            Mr.append(hl.numpy())
+        gu, = torch.autograd.grad(upper(pt), pt)
+        return np.array(Hr), np.array(Mr), gu.numpy()
+
+    def series(H, K, alpha):
+        A = np.eye(d) - alpha * H
+        S, P = np.zeros_like(H), np.eye(d)
+        for _ in range(K + 1):
+            S += P
+            P = P @ A
+        return alpha * S
+
+    H2, M2, gv = dense(ft_wl, v, w)
+    H1, M1, _ = dense(pre_wl, w, theta)
+    K1, a1, K2, a2 = 4, 0.06, 3, 0.09
+    u = -M2.T @ (series(H2, K2, a2) @ gv)
+    expect = -M1.T @ (series(H1, K1, a1) @ u)
+    got = orc.hypergrad_chain3(pre, ft, w, theta, v, K1, a1, K2, a2)
+    assert rel_l2(got, expect) < 1e-10
+    assert rel_l2(orc.best_response_neumann(ft, v, w, gv, K2, a2), u) < 1e-11

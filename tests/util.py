@@ -7,7 +7,8 @@ from oracle import betty_oracle as orc
 def oracle_problem(wl) -> "orc.Problem":
     return orc.Problem(dims=wl.dims, act=wl.act, loss=wl.loss, hp=wl.hp, has_bias=wl.has_bias,
                        X_tr=wl.X_tr, X_val=wl.X_val, y_tr=wl.y_tr, y_val=wl.y_val,
-                       t_tr=wl.t_tr, t_val=wl.t_val, wnet_hidden=wl.wnet_hidden)
+                       t_tr=wl.t_tr, t_val=wl.t_val, wnet_hidden=wl.wnet_hidden,
+                       prox_rho=wl.prox_rho, prox_skip_last=wl.prox_skip_last)
 
 
 def rel_l2(x, ref):
