@@ -64,7 +64,13 @@ typedef enum {
 
 typedef enum { BETTY_ACT_NONE = 0, BETTY_ACT_RELU = 1, BETTY_ACT_GELU_ERF = 2 } betty_act;
 typedef enum { BETTY_LOSS_MSE = 0, BETTY_LOSS_SOFTMAX_CE = 1 } betty_loss;
-typedef enum { BETTY_HP_L2_DECAY = 0, BETTY_HP_REWEIGHT_NET = 1 } betty_hp;
+/* What the upper-level variable `lambda` is (length: betty_num_hyper):
+ *  L2_DECAY      per-parameter log weight decay, cost term sum_j exp(lambda_j) w_j^2  (App. D.1)
+ *  REWEIGHT_NET  parameters of the 1-H-1 sample-weighting net fed the detached loss    (Sec. 4.1)
+ *  PROXIMAL      anchor parameters a, cost term sum_j rho_j (w_j - a_j)^2: the finetuning level
+ *                of the three-level program of Sec. 4.3, whose anchor is the optimum of the
+ *                pretraining level (length d, same layout as w)                               */
+typedef enum { BETTY_HP_L2_DECAY = 0, BETTY_HP_REWEIGHT_NET = 1, BETTY_HP_PROXIMAL = 2 } betty_hp;
 /* Arithmetic of the GEMMs: fp32 operands, or operands rounded to bf16 (round to nearest
  * even) with fp32 accumulation.  Loss math, reductions and all parameter-shaped vectors
  * are fp32 in both.  The finite-difference variant always uses fp32 operands. */
@@ -80,7 +86,9 @@ typedef struct {
   betty_prec prec;
   int batch_train;     /* samples in the lower (train) batch                            */
   int batch_val;       /* samples in the upper (validation) batch                       */
-  int wnet_hidden;     /* H of the 1-H-1 weight net (ignored for L2 decay)              */
+  int wnet_hidden;     /* H of the 1-H-1 weight net (REWEIGHT_NET only)                 */
+  float prox_rho;      /* PROXIMAL only: rho >= 0                                       */
+  int prox_skip_last;  /* PROXIMAL only: non-zero = rho_j is 0 on the last layer's W, b  */
 } betty_problem_desc;
 
 typedef struct {
@@ -152,6 +160,31 @@ betty_status betty_hypergrad_fd(betty_handle h, const float* w, const float* lam
  * zero residual freezes the iterate (no division by zero). */
 betty_status betty_hypergrad_cg(betty_handle h, const float* w, const float* lambda, int K,
                                 float* dlambda);
+
+/* The base operation of Sec. 3.2 (Eq. 3-4) on an arbitrary vector: out = (dw* / dlambda) u
+ *   = -(d^2 L_L / dlambda dw) q,  q = alpha * sum_{j<=K} (I - alpha H)^j u,
+ * i.e. betty_hypergrad_neumann with the device vector u (d floats) in place of grad_w L_U(w).
+ * This is one factor of a path product of Eq. 2: a program with more than two levels applies it
+ * once per lower-to-upper edge, from the right.  out has betty_num_hyper entries and must not
+ * overlap w, lambda or u.  Same argument checks as betty_hypergrad_neumann. */
+betty_status betty_best_response_neumann(betty_handle h, const float* w, const float* lambda,
+                                         const float* u, int K, float alpha, float* out);
+
+/* Three-level chain theta -> w*(theta) -> v*(w*) -> L_U(v*) (Eq. 2 with its single path; the
+ * reweight / pretrain / finetune program of Sec. 4.3):
+ *   dtheta = (dw* / dtheta) (dv* / dw) grad_v L_U(v),
+ * evaluated from the right with two Neumann best-response products.
+ *   h_finetune  BETTY_HP_PROXIMAL handle: parameters v, anchor w, its train batch is the
+ *               finetuning data and its validation batch carries L_U
+ *   h_pretrain  handle of the pretraining problem: parameters w, upper variable theta
+ *               (REWEIGHT_NET or L2_DECAY); only its train batch is used
+ * Both handles must describe the same number of parameters and be bound to the same stream.
+ * w, v: d floats; theta, dtheta: betty_num_hyper(h_pretrain) floats; all device pointers.
+ * Errors are reported on h_pretrain (betty_last_error). */
+betty_status betty_hypergrad_chain3(betty_handle h_pretrain, betty_handle h_finetune, const float* w,
+                                    const float* theta, const float* v, int K_pretrain,
+                                    float alpha_pretrain, int K_finetune, float alpha_finetune,
+                                    float* dtheta);
 
 /* ---- the optimisation steps around the path (Sec. 3.3; optimisers as in App. C) ----------- */
 

@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("BETTY_HIP_LIBRARY") or os.path.join(_HERE, "libbetty_
 
 ACT = {"none": 0, "relu": 1, "gelu": 2}
 LOSS = {"mse": 0, "ce": 1}
-HP = {"l2": 0, "reweight": 1}
+HP = {"l2": 0, "reweight": 1, "proximal": 2}
 PREC = {"fp32": 0, "bf16": 1}
 
 OK, EINVAL, ENULL, ESHAPE, EWORKSPACE, EALIGN, EUNSUPPORTED, EDEVICE = 0, -1, -2, -3, -4, -5, -6, -7
@@ -29,7 +29,8 @@ KIND_NAMES = ["gemm", "epilogue", "loss", "shadow", "vector", "reduce", "wnet", 
 class ProblemDesc(C.Structure):
     _fields_ = [("n_layers", C.c_int), ("dims", C.POINTER(C.c_int)), ("has_bias", C.c_int),
                 ("act", C.c_int), ("loss", C.c_int), ("hp", C.c_int), ("prec", C.c_int),
-                ("batch_train", C.c_int), ("batch_val", C.c_int), ("wnet_hidden", C.c_int)]
+                ("batch_train", C.c_int), ("batch_val", C.c_int), ("wnet_hidden", C.c_int),
+                ("prox_rho", C.c_float), ("prox_skip_last", C.c_int)]
 
 
 class Batch(C.Structure):
@@ -80,6 +81,8 @@ def load_library():
     lib.betty_hypergrad_neumann.argtypes = [vp, f32p, f32p, C.c_int, C.c_float, f32p]
     lib.betty_hypergrad_fd.argtypes = [vp, f32p, f32p, C.c_int, C.c_float, C.c_float, f32p]
     lib.betty_hypergrad_cg.argtypes = [vp, f32p, f32p, C.c_int, f32p]
+    lib.betty_best_response_neumann.argtypes = [vp, f32p, f32p, f32p, C.c_int, C.c_float, f32p]
+    lib.betty_hypergrad_chain3.argtypes = [vp, vp, f32p, f32p, f32p, C.c_int, C.c_float, C.c_int, C.c_float, f32p]
     lib.betty_lower_sgd_step.argtypes = [vp, f32p, f32p, f32p, C.c_float, C.c_float, C.c_float, f32p]
     lib.betty_upper_adam_step.argtypes = [vp, f32p, f32p, f32p, f32p, C.c_int, C.c_float, C.c_float, C.c_float, C.c_float]
     lib.betty_apply_label_noise.argtypes = [vp, vp, vp, vp, C.c_double, C.c_int, vp, vp]
@@ -87,7 +90,8 @@ def load_library():
     lib.betty_profile_collect.argtypes = [vp]
     lib.betty_profile_get.argtypes = [vp, C.c_int, C.POINTER(ProfileRec)]
     for name in ("betty_lower_grad", "betty_upper_grad", "betty_hvp", "betty_mixed_vjp",
-                 "betty_hypergrad_neumann", "betty_hypergrad_fd", "betty_hypergrad_cg", "betty_lower_sgd_step", "betty_upper_adam_step", "betty_apply_label_noise",
+                 "betty_hypergrad_neumann", "betty_hypergrad_fd", "betty_hypergrad_cg", "betty_best_response_neumann",
+                 "betty_hypergrad_chain3", "betty_lower_sgd_step", "betty_upper_adam_step", "betty_apply_label_noise",
                  "betty_profile_enable", "betty_profile_collect", "betty_profile_get"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -110,11 +114,12 @@ class Betty:
     """One problem description bound to a workspace and the current torch stream."""
 
     def __init__(self, dims: Sequence[int], act="relu", loss="ce", hp="l2", prec="fp32", has_bias=True,
-                 batch_train=1, batch_val=1, wnet_hidden=100, device="cuda:0", stream=None):
+                 batch_train=1, batch_val=1, wnet_hidden=100, prox_rho=0.0, prox_skip_last=False,
+                 device="cuda:0", stream=None):
         self.lib = load_library()
         self._dims = (C.c_int * len(dims))(*dims)
         desc = ProblemDesc(len(dims) - 1, self._dims, int(has_bias), ACT[act], LOSS[loss], HP[hp], PREC[prec],
-                           batch_train, batch_val, wnet_hidden)
+                           batch_train, batch_val, wnet_hidden, float(prox_rho), int(bool(prox_skip_last)))
         self.h = C.c_void_p()
         st = self.lib.betty_create(C.byref(desc), C.byref(self.h))
         if st != OK:
@@ -205,6 +210,25 @@ class Betty:
                                                 _ptr(o, torch.float32, self.n_hyper)))
         return o
 
+    def betty_best_response_neumann(self, w, lam, u, K, alpha, out=None):
+        o = out if out is not None else self._vec(self.n_hyper)
+        self._check(self.lib.betty_best_response_neumann(self.h, _ptr(w, torch.float32, self.d),
+                                                         _ptr(lam, torch.float32, self.n_hyper),
+                                                         _ptr(u, torch.float32, self.d), int(K), float(alpha),
+                                                         _ptr(o, torch.float32, self.n_hyper)))
+        return o
+
+    def betty_hypergrad_chain3(self, finetune: "Betty", w, theta, v, K_pretrain, alpha_pretrain, K_finetune,
+                               alpha_finetune, out=None):
+        """self is the pretraining problem's handle, `finetune` the proximal one."""
+        o = out if out is not None else self._vec(self.n_hyper)
+        self._check(self.lib.betty_hypergrad_chain3(self.h, finetune.h, _ptr(w, torch.float32, self.d),
+                                                    _ptr(theta, torch.float32, self.n_hyper),
+                                                    _ptr(v, torch.float32, self.d), int(K_pretrain),
+                                                    float(alpha_pretrain), int(K_finetune), float(alpha_finetune),
+                                                    _ptr(o, torch.float32, self.n_hyper)))
+        return o
+
     def betty_lower_sgd_step(self, w, lam, momentum, lr, mu, weight_decay=0.0, want_loss=False):
         loss = self._vec(1) if want_loss else None
         self._check(self.lib.betty_lower_sgd_step(self.h, _ptr(w, torch.float32, self.d),
@@ -246,7 +270,8 @@ class Betty:
 def from_workload(wl, device="cuda:0") -> "Betty":
     """Creates a handle for a seeded workload and uploads its batches."""
     b = Betty(wl.dims, act=wl.act, loss=wl.loss, hp=wl.hp, prec=wl.prec, has_bias=wl.has_bias,
-              batch_train=wl.X_tr.shape[0], batch_val=wl.X_val.shape[0], wnet_hidden=wl.wnet_hidden, device=device)
+              batch_train=wl.X_tr.shape[0], batch_val=wl.X_val.shape[0], wnet_hidden=wl.wnet_hidden,
+              prox_rho=wl.prox_rho, prox_skip_last=wl.prox_skip_last, device=device)
     dev = b.device
 
     def up(a, dt):

@@ -77,15 +77,16 @@ struct betty_handle_s {
   OperandSet sets[2];        // [0]: element type of desc.prec; [1]: fp32 set for finite differences when prec is bf16
   size_t vec_g = 0, vec_v = 0, vec_p = 0, vec_Hv = 0, vec_wpm = 0, vec_Gm = 0;
   size_t partials = 0, scalars = 0;
+  size_t logrho = 0;         // proximal cost: log(rho_j) per parameter (a large negative value where rho_j = 0)
   // a hypergradient call repeated with the same arguments is replayed from a captured HIP graph
   struct GraphSlot {
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
-    const void* w = nullptr; const void* lam = nullptr; void* out = nullptr;
+    const void* w = nullptr; const void* lam = nullptr; const void* u = nullptr; void* out = nullptr;
     int K = -1; float alpha = 0.f, eps = 0.f;
     int seen = 0;
   };
-  GraphSlot graph_neumann, graph_fd, graph_cg;
+  GraphSlot graph_neumann, graph_fd, graph_cg, graph_br;
   bool use_graphs = true;
   int tune_target_blocks = 256, tune_tile128_min = 512;   // see plan_chain (measured on 512x4096x8192: 64-tiles beat 128-tiles until the grid is several waves deep)
   int tune_wgrad_cfg = GEMM_64x1;
@@ -180,9 +181,22 @@ void plan(betty_handle h) {
   const size_t vb = h->d * 4;
   h->vec_g = pl.take(vb); h->vec_v = pl.take(vb); h->vec_p = pl.take(vb); h->vec_Hv = pl.take(vb);
   h->vec_wpm = pl.take(vb); h->vec_Gm = pl.take(vb);
+  if (h->desc.hp == BETTY_HP_PROXIMAL) h->logrho = pl.take(vb);
   h->partials = pl.take(1024 * 8);
   h->scalars = pl.take(256);
   h->ws_need = pl.off;
+}
+
+// The lower cost's parameter-diagonal term is sum_j exp(c_j) (.)^2 with c = lambda for L2 decay and
+// c = log(rho) for the proximal cost; the reweighting cost has none.
+const float* diag_log(betty_handle h, const float* lambda) {
+  if (h->desc.hp == BETTY_HP_L2_DECAY) return lambda;
+  if (h->desc.hp == BETTY_HP_PROXIMAL) return h->f(h->logrho);
+  return nullptr;
+}
+// the weight-net parameters, for the cost that has a weight net
+const float* wnet_theta(betty_handle h, const float* lambda) {
+  return h->desc.hp == BETTY_HP_REWEIGHT_NET ? lambda : nullptr;
 }
 
 OperandSet& fd_operands(betty_handle h) { return h->sets[1].present ? h->sets[1] : h->sets[0]; }
@@ -490,16 +504,22 @@ void hvp_cached(betty_handle h, OperandSet& os, const float* vflat, const WgradS
 // full first-order gradient of the lower cost at w (operand copies of w already made)
 void lower_grad_seq(betty_handle h, OperandSet& os, const float* w, const float* lam, float* grad,
                     float* loss_or_null, const float* omega_fixed = nullptr) {
-  const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
-  forward_and_loss(h, os, SIDE_TRAIN, w, l2 ? nullptr : lam, omega_fixed);
+  const float* dl = diag_log(h, lam);
+  // what the diagonal term multiplies: w itself, or its distance to the anchor (kept in vec_g)
+  const float* x = w;
+  if (h->desc.hp == BETTY_HP_PROXIMAL) {
+    launch_diff(h->ctx, w, lam, h->f(h->vec_g), h->d);
+    x = h->f(h->vec_g);
+  }
+  forward_and_loss(h, os, SIDE_TRAIN, w, wnet_theta(h, lam), omega_fixed);
   backward_chain(h, os, SIDE_TRAIN);
-  WgradSink k{EPI_WGRAD, grad, l2 ? lam : nullptr, l2 ? w : nullptr, nullptr, nullptr, 0.f, false};
+  WgradSink k{EPI_WGRAD, grad, dl, dl ? x : nullptr, nullptr, nullptr, 0.f, false};
   wgrad_batch(h, os, 0, false, k);
   if (loss_or_null) {
     float* add = nullptr;
-    if (l2) {
+    if (dl) {
       add = h->f(h->scalars) + 8;
-      launch_l2_cost(h->ctx, lam, w, h->d, h->at<double>(h->partials), add);
+      launch_l2_cost(h->ctx, dl, x, h->d, h->at<double>(h->partials), add);
     }
     launch_weighted_loss_sum(h->ctx, h->f(os.side[0].s), h->f(os.side[0].ell), os.side[0].B, add, loss_or_null);
   }
@@ -511,7 +531,7 @@ void lower_grad_seq(betty_handle h, OperandSet& os, const float* w, const float*
 void upper_grad_seq(betty_handle h, OperandSet& os, const float* w, const float* lam, bool with_lower,
                     const WgradSink& sink, float* loss_or_null) {
   const int sides = with_lower ? SIDE_BOTH : SIDE_VAL;
-  forward_and_loss(h, os, sides, w, h->desc.hp == BETTY_HP_L2_DECAY ? nullptr : lam);
+  forward_and_loss(h, os, sides, w, wnet_theta(h, lam));
   backward_chain(h, os, sides);
   wgrad_batch(h, os, 1, false, sink);
   if (loss_or_null)
@@ -520,7 +540,7 @@ void upper_grad_seq(betty_handle h, OperandSet& os, const float* w, const float*
 
 // forward/backward cache of the train batch for the R-op passes (no parameter gradient)
 void prepare_lower(betty_handle h, OperandSet& os, const float* w, const float* lam) {
-  forward_and_loss(h, os, SIDE_TRAIN, w, h->desc.hp == BETTY_HP_L2_DECAY ? nullptr : lam);
+  forward_and_loss(h, os, SIDE_TRAIN, w, wnet_theta(h, lam));
   backward_chain(h, os, SIDE_TRAIN);
 }
 
@@ -584,24 +604,27 @@ static void drop_graph(betty_handle_s::GraphSlot& g) {
   g = betty_handle_s::GraphSlot();
 }
 
-static void drop_graphs(betty_handle h) { drop_graph(h->graph_neumann); drop_graph(h->graph_fd); drop_graph(h->graph_cg); }
+static void drop_graphs(betty_handle h) {
+  drop_graph(h->graph_neumann); drop_graph(h->graph_fd); drop_graph(h->graph_cg); drop_graph(h->graph_br);
+}
 
 // Runs `body` (which only enqueues kernels on the bound stream) directly the first time a given
 // argument set is seen, captures it into a graph the second time, and replays the graph from then
 // on.  Any capture failure switches graphs off for the handle and runs the body directly.
 template <typename Body>
 static betty_status run_cached(betty_handle h, betty_handle_s::GraphSlot& g, const void* w, const void* lam,
-                               void* out, int K, float alpha, float eps, Body body) {
+                               const void* u, void* out, int K, float alpha, float eps, Body body) {
   const bool eligible = h->use_graphs && !h->ctx.profiling && h->ctx.stream != nullptr;
   if (!eligible) { body(); return finish(h); }
-  const bool same = g.seen > 0 && g.w == w && g.lam == lam && g.out == out && g.K == K && g.alpha == alpha && g.eps == eps;
+  const bool same = g.seen > 0 && g.w == w && g.lam == lam && g.u == u && g.out == out && g.K == K &&
+                    g.alpha == alpha && g.eps == eps;
   if (same && g.exec) {
     if (hipGraphLaunch(g.exec, h->ctx.stream) != hipSuccess) return fail(h, BETTY_EDEVICE, "hipGraphLaunch failed");
     return BETTY_OK;
   }
   if (!same) {
     drop_graph(g);
-    g.w = w; g.lam = lam; g.out = out; g.K = K; g.alpha = alpha; g.eps = eps; g.seen = 1;
+    g.w = w; g.lam = lam; g.u = u; g.out = out; g.K = K; g.alpha = alpha; g.eps = eps; g.seen = 1;
     body();
     return finish(h);
   }
@@ -640,6 +663,47 @@ static betty_status check_hyper_args(betty_handle h, const float* w, const float
   return BETTY_OK;
 }
 
+// out = (dw* / dlambda) u by the K-step Neumann series and the mixed VJP; u = grad_w L_U(w) on the
+// validation batch when u_or_null is null.  Only enqueues launches on the handle's stream.
+static void neumann_seq(betty_handle h, const float* w, const float* lambda, const float* u_or_null, int K,
+                        float alpha, float* out) {
+  OperandSet& os = h->sets[0];
+  const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY, rw = h->desc.hp == BETTY_HP_REWEIGHT_NET;
+  const float* dl = diag_log(h, lambda);
+  float* v = h->f(h->vec_v); float* p = h->f(h->vec_p);
+  const bool need_lower = K > 0 || rw;      // forward/backward cache of the train batch
+  make_weight_operands(h, os, w);
+  if (u_or_null) {
+    if (need_lower) prepare_lower(h, os, w, lambda);
+    launch_scale_copy(h->ctx, u_or_null, 1.f, v, h->d);
+    launch_scale_copy(h->ctx, u_or_null, 1.f, p, h->d);
+    if (K > 0) make_shadows(h, os, u_or_null, 1.f, &os.Vn, &os.Vt);
+  } else {
+    // g = grad_w L_U lands directly in v and p, with the operand copies of v for the first product
+    WgradSink init{EPI_WGRAD_INIT, nullptr, nullptr, nullptr, v, p, 0.f, K > 0};
+    upper_grad_seq(h, os, w, lambda, need_lower, init, nullptr);
+  }
+  for (int k = 0; k < K; ++k) {
+    // v <- v - alpha (H v), p <- p + v fused into the weight-gradient epilogues of the product;
+    // for L2 decay the last step also applies the mixed VJP, so only d(lambda) is written
+    const bool last = k + 1 == K;
+    if (last && l2) {
+      WgradSink fin{EPI_WGRAD_NEUMANN_L2, out, lambda, w, v, p, alpha, false};
+      hvp_cached(h, os, v, fin);
+    } else {
+      WgradSink step{EPI_WGRAD_NEUMANN, nullptr, dl, nullptr, v, p, alpha, !last};
+      hvp_cached(h, os, v, step);
+    }
+  }
+  if (l2) {
+    if (K == 0) launch_mixed_l2(h->ctx, lambda, w, p, alpha, out, h->d);
+  } else if (rw) {
+    mixed_reweight_seq(h, os, lambda, p, alpha, out);
+  } else {
+    launch_mixed_prox(h->ctx, h->f(h->logrho), p, alpha, out, h->d);
+  }
+}
+
 extern "C" {
 
 betty_status betty_create(const betty_problem_desc* desc, betty_handle* out) {
@@ -653,7 +717,9 @@ betty_status betty_create(const betty_problem_desc* desc, betty_handle* out) {
     return BETTY_ESHAPE;
   if (desc->act < BETTY_ACT_NONE || desc->act > BETTY_ACT_GELU_ERF) return BETTY_EINVAL;
   if (desc->loss != BETTY_LOSS_MSE && desc->loss != BETTY_LOSS_SOFTMAX_CE) return BETTY_EINVAL;
-  if (desc->hp != BETTY_HP_L2_DECAY && desc->hp != BETTY_HP_REWEIGHT_NET) return BETTY_EINVAL;
+  if (desc->hp != BETTY_HP_L2_DECAY && desc->hp != BETTY_HP_REWEIGHT_NET && desc->hp != BETTY_HP_PROXIMAL)
+    return BETTY_EINVAL;
+  if (desc->hp == BETTY_HP_PROXIMAL && !(std::isfinite(desc->prox_rho) && desc->prox_rho >= 0.f)) return BETTY_EINVAL;
   if (desc->prec != BETTY_PREC_FP32 && desc->prec != BETTY_PREC_BF16_FP32ACC) return BETTY_EINVAL;
   if (desc->hp == BETTY_HP_REWEIGHT_NET && (desc->wnet_hidden < 1 || desc->wnet_hidden > 65536)) return BETTY_ESHAPE;
 
@@ -675,7 +741,7 @@ betty_status betty_create(const betty_problem_desc* desc, betty_handle* out) {
     h->max_np = std::max(h->max_np, std::max(li.n_in_p, li.n_out_p));
   }
   h->d = off;
-  h->n_hyper = desc->hp == BETTY_HP_L2_DECAY ? h->d : (size_t)3 * desc->wnet_hidden + 1;
+  h->n_hyper = desc->hp == BETTY_HP_REWEIGHT_NET ? (size_t)3 * desc->wnet_hidden + 1 : h->d;
   h->max_Bp = std::max(padup(desc->batch_train), padup(desc->batch_val));
   // tuning overrides for experiments: BETTY_TUNE="wgrad=<cfg>,tile128=<n>,blocks=<n>" (see plan_chain)
   if (const char* t = getenv("BETTY_TUNE")) {
@@ -712,6 +778,14 @@ betty_status betty_bind(betty_handle h, void* workspace, size_t bytes, void* hip
   h->bound = true;
   h->batches = false;
   launch_fill_zero(h->ctx, h->ws, h->ws_need);
+  if (h->desc.hp == BETTY_HP_PROXIMAL) {
+    // exp(-200) is exactly 0 in fp32, so parameters outside the proximal term get no curvature
+    const LayerInfo& last = h->layers[h->L - 1];
+    const size_t cut = h->desc.prox_skip_last ? last.w_off : h->d;
+    const float lr = h->desc.prox_rho > 0.f ? std::log(h->desc.prox_rho) : -200.f;
+    launch_fill_value(h->ctx, h->f(h->logrho), std::max(lr, -200.f), cut);
+    if (cut < h->d) launch_fill_value(h->ctx, h->f(h->logrho) + cut, -200.f, h->d - cut);
+  }
   return finish(h);
 }
 
@@ -777,8 +851,8 @@ betty_status betty_hvp(betty_handle h, const float* w, const float* lambda, cons
   make_weight_operands(h, os, w);
   prepare_lower(h, os, w, lambda);
   make_shadows(h, os, v, 1.f, &os.Vn, &os.Vt);
-  const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
-  WgradSink k{EPI_WGRAD, Hv, l2 ? lambda : nullptr, l2 ? v : nullptr, nullptr, nullptr, 0.f, false};
+  const float* dl = diag_log(h, lambda);
+  WgradSink k{EPI_WGRAD, Hv, dl, dl ? v : nullptr, nullptr, nullptr, 0.f, false};
   hvp_cached(h, os, v, k);
   return finish(h);
 }
@@ -794,6 +868,10 @@ betty_status betty_mixed_vjp(betty_handle h, const float* w, const float* lambda
     launch_mixed_l2(h->ctx, lambda, w, q, 1.f, out, h->d);
     return finish(h);
   }
+  if (h->desc.hp == BETTY_HP_PROXIMAL) {
+    launch_mixed_prox(h->ctx, h->f(h->logrho), q, 1.f, out, h->d);
+    return finish(h);
+  }
   OperandSet& os = h->sets[0];
   make_weight_operands(h, os, w);
   forward_and_loss(h, os, SIDE_TRAIN, w, lambda);
@@ -804,33 +882,43 @@ betty_status betty_mixed_vjp(betty_handle h, const float* w, const float* lambda
 betty_status betty_hypergrad_neumann(betty_handle h, const float* w, const float* lambda, int K, float alpha,
                                      float* dlambda) {
   CHECK(check_hyper_args(h, w, lambda, K, alpha, dlambda));
-  auto body = [=]() {
-    OperandSet& os = h->sets[0];
-    const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
-    float* v = h->f(h->vec_v); float* p = h->f(h->vec_p);
-    make_weight_operands(h, os, w);
-    // g = grad_w L_U lands directly in v and p, with the operand copies of v for the first product
-    WgradSink init{EPI_WGRAD_INIT, nullptr, nullptr, nullptr, v, p, 0.f, K > 0};
-    upper_grad_seq(h, os, w, lambda, K > 0 || !l2, init, nullptr);
-    for (int k = 0; k < K; ++k) {
-      // v <- v - alpha (H v), p <- p + v fused into the weight-gradient epilogues of the product;
-      // for L2 decay the last step also applies the mixed VJP, so only d(lambda) is written
-      const bool last = k + 1 == K;
-      if (last && l2) {
-        WgradSink fin{EPI_WGRAD_NEUMANN_L2, dlambda, lambda, w, v, p, alpha, false};
-        hvp_cached(h, os, v, fin);
-      } else {
-        WgradSink step{EPI_WGRAD_NEUMANN, nullptr, l2 ? lambda : nullptr, nullptr, v, p, alpha, !last};
-        hvp_cached(h, os, v, step);
-      }
-    }
-    if (l2) {
-      if (K == 0) launch_mixed_l2(h->ctx, lambda, w, p, alpha, dlambda, h->d);
-    } else {
-      mixed_reweight_seq(h, os, lambda, p, alpha, dlambda);
-    }
-  };
-  return run_cached(h, h->graph_neumann, w, lambda, dlambda, K, alpha, 0.f, body);
+  auto body = [=]() { neumann_seq(h, w, lambda, nullptr, K, alpha, dlambda); };
+  return run_cached(h, h->graph_neumann, w, lambda, nullptr, dlambda, K, alpha, 0.f, body);
+}
+
+betty_status betty_best_response_neumann(betty_handle h, const float* w, const float* lambda, const float* u, int K,
+                                         float alpha, float* out) {
+  CHECK(check_hyper_args(h, w, lambda, K, alpha, out));
+  CHECK(check_vec(h, u, "u"));
+  if (overlaps(out, h->n_hyper * 4, u, h->d * 4)) return fail(h, BETTY_EINVAL, "out overlaps u");
+  auto body = [=]() { neumann_seq(h, w, lambda, u, K, alpha, out); };
+  return run_cached(h, h->graph_br, w, lambda, u, out, K, alpha, 0.f, body);
+}
+
+betty_status betty_hypergrad_chain3(betty_handle hp, betty_handle hf, const float* w, const float* theta,
+                                    const float* v, int K_pre, float alpha_pre, int K_ft, float alpha_ft,
+                                    float* dtheta) {
+  if (!hp || !hf) return BETTY_ENULL;
+  CHECK(check_hyper_args(hp, w, theta, K_pre, alpha_pre, dtheta));
+  if (check_ready(hf) != BETTY_OK) return fail(hp, BETTY_EWORKSPACE, "finetune handle: %s", hf->err.c_str());
+  if (hf->desc.hp != BETTY_HP_PROXIMAL) return fail(hp, BETTY_EINVAL, "the finetune handle must be BETTY_HP_PROXIMAL");
+  if (hf->d != hp->d) return fail(hp, BETTY_ESHAPE, "finetune handle has %zu parameters, pretrain handle %zu", hf->d, hp->d);
+  if (hf->ctx.stream != hp->ctx.stream) return fail(hp, BETTY_EINVAL, "both handles must be bound to the same stream");
+  CHECK(check_vec(hp, v, "v"));
+  if (K_ft < 0) return fail(hp, BETTY_EINVAL, "K_finetune must be >= 0 (got %d)", K_ft);
+  if (!std::isfinite(alpha_ft)) return fail(hp, BETTY_EINVAL, "alpha_finetune must be finite");
+  if (overlaps(dtheta, hp->n_hyper * 4, v, hp->d * 4)) return fail(hp, BETTY_EINVAL, "dtheta overlaps v");
+  // rightmost factor first: u = (dv* / dw) grad_v L_U(v) on the finetuning problem (anchor w),
+  // kept in that handle's workspace; then (dw* / dtheta) u on the pretraining problem
+  float* u = hf->f(hf->vec_g);
+  neumann_seq(hf, v, w, nullptr, K_ft, alpha_ft, u);
+  if (hf->ctx.first_error != hipSuccess) {
+    betty_status st = fail(hp, BETTY_EDEVICE, "HIP error on the finetune handle: %s", hipGetErrorString(hf->ctx.first_error));
+    hf->ctx.first_error = hipSuccess;
+    return st;
+  }
+  neumann_seq(hp, w, theta, u, K_pre, alpha_pre, dtheta);
+  return finish(hp);
 }
 
 betty_status betty_hypergrad_fd(betty_handle h, const float* w, const float* lambda, int K, float alpha,
@@ -840,14 +928,14 @@ betty_status betty_hypergrad_fd(betty_handle h, const float* w, const float* lam
   auto body = [=]() {
     OperandSet& os = fd_operands(h);
     SideBuf& sb = os.side[0];
-    const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
+    const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY, rw = h->desc.hp == BETTY_HP_REWEIGHT_NET;
     float* v = h->f(h->vec_v); float* p = h->f(h->vec_p); float* Gp = h->f(h->vec_Hv);
     float* Gm = h->f(h->vec_Gm); float* wpm = h->f(h->vec_wpm);
     float* nrm2 = h->f(h->scalars); float* eps = h->f(h->scalars) + 1;
     make_weight_operands(h, os, w);
     WgradSink init{EPI_WGRAD_INIT, nullptr, nullptr, nullptr, v, p, 0.f, false};
     const float* omega_bar = nullptr;
-    if (l2) {
+    if (!rw) {
       upper_grad_seq(h, os, w, nullptr, false, init, nullptr);
     } else {
       // the reweighting cost holds its sample weights constant in w: evaluate them (and the loss fed
@@ -874,6 +962,9 @@ betty_status betty_hypergrad_fd(betty_handle h, const float* w, const float* lam
     launch_fd_eps(h->ctx, nrm2, eps_scale, alpha, eps);
     if (l2) {
       launch_mixed_l2_fd(h->ctx, lambda, w, p, alpha, eps, dlambda, h->d);
+    } else if (!rw) {
+      // grad_a of the proximal cost is linear in w, so its central difference along q is exact
+      launch_mixed_prox(h->ctx, h->f(h->logrho), p, alpha, dlambda, h->d);
     } else {
       // grad_theta L_L(w') = (1/B) sum_i l_i(w') dR(lbar_i)/dtheta, so its central difference along
       // q = alpha p needs only the per-sample losses at w +- eps q
@@ -890,36 +981,38 @@ betty_status betty_hypergrad_fd(betty_handle h, const float* w, const float* lam
                             h->desc.wnet_hidden, sb.B, 1.0f / (float)sb.B, dlambda);
     }
   };
-  return run_cached(h, h->graph_fd, w, lambda, dlambda, K, alpha, eps_scale, body);
+  return run_cached(h, h->graph_fd, w, lambda, nullptr, dlambda, K, alpha, eps_scale, body);
 }
 
 betty_status betty_hypergrad_cg(betty_handle h, const float* w, const float* lambda, int K, float* dlambda) {
   CHECK(check_hyper_args(h, w, lambda, K, 0.f, dlambda));
   auto body = [=]() {
     OperandSet& os = h->sets[0];
-    const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
+    const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY, rw = h->desc.hp == BETTY_HP_REWEIGHT_NET;
+    const float* dl = diag_log(h, lambda);
     float* r = h->f(h->vec_g); float* d = h->f(h->vec_v); float* q = h->f(h->vec_p); float* Hd = h->f(h->vec_Hv);
     float* sc = h->f(h->scalars);            // sc[0], sc[1]: r.r of the current / next iterate; sc[2]: d.Hd
     double* partials = h->at<double>(h->partials);
     make_weight_operands(h, os, w);
     WgradSink g_out{EPI_WGRAD, r, nullptr, nullptr, nullptr, nullptr, 0.f, false};
-    upper_grad_seq(h, os, w, lambda, K > 0 || !l2, g_out, nullptr);
+    upper_grad_seq(h, os, w, lambda, K > 0 || rw, g_out, nullptr);
     launch_cg_init(h->ctx, r, d, q, h->d);
     launch_sumsq(h->ctx, r, h->d, partials, sc);
     for (int k = 0; k < K; ++k) {
       float* rs = sc + (k & 1);
       float* rs_new = sc + ((k + 1) & 1);
       make_shadows(h, os, d, 1.f, &os.Vn, &os.Vt);
-      WgradSink hd{EPI_WGRAD, Hd, l2 ? lambda : nullptr, l2 ? d : nullptr, nullptr, nullptr, 0.f, false};
+      WgradSink hd{EPI_WGRAD, Hd, dl, dl ? d : nullptr, nullptr, nullptr, 0.f, false};
       hvp_cached(h, os, d, hd);
       launch_dot(h->ctx, d, Hd, h->d, partials, sc + 2);
       launch_cg_step(h->ctx, q, r, d, Hd, rs, sc + 2, h->d, partials, rs_new);
       if (k + 1 < K) launch_cg_dir(h->ctx, d, r, rs, rs_new, h->d);
     }
     if (l2) launch_mixed_l2(h->ctx, lambda, w, q, 1.f, dlambda, h->d);
-    else mixed_reweight_seq(h, os, lambda, q, 1.f, dlambda);
+    else if (rw) mixed_reweight_seq(h, os, lambda, q, 1.f, dlambda);
+    else launch_mixed_prox(h->ctx, h->f(h->logrho), q, 1.f, dlambda, h->d);
   };
-  return run_cached(h, h->graph_cg, w, lambda, dlambda, K, 0.f, -1.f, body);
+  return run_cached(h, h->graph_cg, w, lambda, nullptr, dlambda, K, 0.f, -1.f, body);
 }
 
 betty_status betty_lower_sgd_step(betty_handle h, float* w, const float* lambda, float* momentum, float lr, float mu,
@@ -933,20 +1026,27 @@ betty_status betty_lower_sgd_step(betty_handle h, float* w, const float* lambda,
       overlaps(momentum, h->d * 4, lambda, h->n_hyper * 4))
     return fail(h, BETTY_EINVAL, "w, momentum and lambda must not overlap");
   OperandSet& os = h->sets[0];
-  const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY;
+  const bool prox = h->desc.hp == BETTY_HP_PROXIMAL;
+  const float* dl = diag_log(h, lambda);
   make_weight_operands(h, os, w);
-  forward_and_loss(h, os, SIDE_TRAIN, w, l2 ? nullptr : lambda);
+  forward_and_loss(h, os, SIDE_TRAIN, w, wnet_theta(h, lambda));
   backward_chain(h, os, SIDE_TRAIN);
   if (loss_or_null) {                      // the cost at the w before the step
     float* add = nullptr;
-    if (l2) {
+    if (dl) {
+      const float* x = w;
+      if (prox) {
+        launch_diff(h->ctx, w, lambda, h->f(h->vec_g), h->d);
+        x = h->f(h->vec_g);
+      }
       add = h->f(h->scalars) + 8;
-      launch_l2_cost(h->ctx, lambda, w, h->d, h->at<double>(h->partials), add);
+      launch_l2_cost(h->ctx, dl, x, h->d, h->at<double>(h->partials), add);
     }
     launch_weighted_loss_sum(h->ctx, h->f(os.side[0].s), h->f(os.side[0].ell), os.side[0].B, add, loss_or_null);
   }
   // momentum and parameters are updated in the epilogue of the weight-gradient launch
-  WgradSink k{EPI_WGRAD_SGD, nullptr, l2 ? lambda : nullptr, nullptr, momentum, w, lr, false};
+  // (the proximal term pulls towards the anchor: the epilogue subtracts it from w in that term)
+  WgradSink k{EPI_WGRAD_SGD, nullptr, dl, prox ? lambda : nullptr, momentum, w, lr, false};
   k.beta = mu; k.gamma = weight_decay;
   wgrad_batch(h, os, 0, false, k);
   return finish(h);

@@ -133,6 +133,7 @@ __device__ __forceinline__ void epi_prefetch(const Epilogue& e, int M, int N, in
       R.a[k] = ok ? e.v[o] : 0.f;
       R.b[k] = ok ? e.p[o] : 0.f;
       R.c[k] = (ok && e.lam) ? e.lam[o] : 0.f;
+      R.d[k] = (ok && e.x) ? e.x[o] : 0.f;
     }
   }
 }
@@ -215,7 +216,7 @@ __device__ __forceinline__ void epi_finish(const Epilogue& e, int M, int N, int 
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
       float gk = acc[k] + e.gamma * R.b[k];
-      if (e.lam) gk += 2.f * expf(R.c[k]) * R.b[k];
+      if (e.lam) gk += 2.f * expf(R.c[k]) * (R.b[k] - R.d[k]);     // x: anchor of a proximal term
       const float mk = e.beta * R.a[k] + gk;
       if (ok[k]) { e.v[of[k]] = mk; e.p[of[k]] = R.b[k] - e.alpha * mk; }
     }
@@ -294,7 +295,7 @@ __device__ void bias_rows(const BiasJob& j, int row) {
     case EPI_WGRAD_SGD: {
       const float wo = j.p[row];
       float gk = acc + j.gamma * wo;
-      if (j.lam) gk += 2.f * expf(j.lam[row]) * wo;
+      if (j.lam) gk += 2.f * expf(j.lam[row]) * (wo - (j.x ? j.x[row] : 0.f));
       const float mk = j.beta * j.v[row] + gk;
       j.v[row] = mk;
       j.p[row] = wo - j.alpha * mk;

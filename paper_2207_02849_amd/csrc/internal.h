@@ -151,6 +151,10 @@ void launch_wnet_theta_vjp(Ctx&, const float* ell, const float* omega, const flo
 void launch_fill_zero(Ctx&, void* p, size_t bytes);
 void launch_scale_copy(Ctx&, const float* src, float scale, float* dst, size_t n);
 void launch_mixed_l2(Ctx&, const float* lam, const float* w, const float* p, float alpha, float* out, size_t n);
+// out = 2 exp(logrho) (alpha p): the mixed VJP of the proximal cost into its anchor
+void launch_mixed_prox(Ctx&, const float* logrho, const float* p, float alpha, float* out, size_t n);
+void launch_diff(Ctx&, const float* a, const float* b, float* out, size_t n);        // out = a - b
+void launch_fill_value(Ctx&, float* p, float value, size_t n);
 void launch_sumsq(Ctx&, const float* x, size_t n, double* partials, float* out_scalar);
 void launch_dot(Ctx&, const float* x, const float* y, size_t n, double* partials, float* out_scalar);
 // conjugate gradient on device scalars: a = rs / dHd (0 if either is 0); q += a d; r -= a Hd; rs_new = r.r

@@ -320,6 +320,31 @@ void launch_mixed_l2(Ctx& ctx, const float* lam, const float* w, const float* p,
   mixed_l2_kernel<<<flat_grid(n), 256, 0, ctx.stream>>>(lam, w, p, alpha, out, n);
 }
 
+__global__ __launch_bounds__(256) void mixed_prox_kernel(const float* logrho, const float* p, float alpha, float* out, size_t n) {
+  FLAT_LOOP(i, n) out[i] = 2.f * expf(logrho[i]) * (alpha * p[i]);
+}
+void launch_mixed_prox(Ctx& ctx, const float* logrho, const float* p, float alpha, float* out, size_t n) {
+  Launch l(ctx, BETTY_K_VECTOR, 0, 12.0 * n);
+  mixed_prox_kernel<<<flat_grid(n), 256, 0, ctx.stream>>>(logrho, p, alpha, out, n);
+}
+
+__global__ __launch_bounds__(256) void diff_kernel(const float* a, const float* b, float* out, size_t n) {
+  FLAT_LOOP(i, n) out[i] = a[i] - b[i];
+}
+void launch_diff(Ctx& ctx, const float* a, const float* b, float* out, size_t n) {
+  Launch l(ctx, BETTY_K_VECTOR, 0, 12.0 * n);
+  diff_kernel<<<flat_grid(n), 256, 0, ctx.stream>>>(a, b, out, n);
+}
+
+__global__ __launch_bounds__(256) void fill_value_kernel(float* p, float value, size_t n) {
+  FLAT_LOOP(i, n) p[i] = value;
+}
+void launch_fill_value(Ctx& ctx, float* p, float value, size_t n) {
+  if (n == 0) return;
+  Launch l(ctx, BETTY_K_VECTOR, 0, 4.0 * n);
+  fill_value_kernel<<<flat_grid(n), 256, 0, ctx.stream>>>(p, value, n);
+}
+
 // two-stage deterministic reductions: per-block partials, then one block in fixed order
 constexpr int RED_BLOCKS = 1024;
 

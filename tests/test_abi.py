@@ -30,10 +30,11 @@ def _create(dims, **kw):
     lib = binding.load_library()
     arr = (C.c_int * len(dims))(*dims)
     args = dict(n_layers=len(dims) - 1, has_bias=1, act=1, loss=1, hp=0, prec=0, batch_train=4, batch_val=4,
-                wnet_hidden=100)
+                wnet_hidden=100, prox_rho=0.0, prox_skip_last=0)
     args.update(kw)
     desc = binding.ProblemDesc(args["n_layers"], arr, args["has_bias"], args["act"], args["loss"], args["hp"],
-                               args["prec"], args["batch_train"], args["batch_val"], args["wnet_hidden"])
+                               args["prec"], args["batch_train"], args["batch_val"], args["wnet_hidden"],
+                               args["prox_rho"], args["prox_skip_last"])
     h = C.c_void_p()
     st = lib.betty_create(C.byref(desc), C.byref(h))
     return lib, st, h
@@ -48,6 +49,9 @@ def test_create_plans_sizes_on_the_host():
     lib, st, h = _create([1024, 512, 512, 10], hp=1, prec=1, wnet_hidden=100)
     assert st == binding.OK and lib.betty_num_params(h) == 792586 and lib.betty_num_hyper(h) == 301
     lib.betty_destroy(h)
+    lib, st, h = _create([12, 7, 3], hp=2, prox_rho=0.01, prox_skip_last=1)        # anchor has the layout of w
+    assert st == binding.OK and lib.betty_num_params(h) == lib.betty_num_hyper(h) == 12 * 7 + 7 + 7 * 3 + 3
+    lib.betty_destroy(h)
 
 
 @pytest.mark.parametrize("kw,expect", [
@@ -58,6 +62,8 @@ def test_create_plans_sizes_on_the_host():
     (dict(hp=3), binding.EINVAL),
     (dict(prec=2), binding.EINVAL),
     (dict(hp=1, wnet_hidden=0), binding.ESHAPE),
+    (dict(hp=2, prox_rho=-1.0), binding.EINVAL),
+    (dict(hp=2, prox_rho=float("nan")), binding.EINVAL),
 ])
 def test_create_rejects_bad_descriptions(kw, expect):
     _, st, h = _create([8, 4, 3], **kw)

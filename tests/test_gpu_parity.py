@@ -69,6 +69,14 @@ def run_all(wl, tol=None, fd=True, big_alpha=None, check_losses=True, stationary
         hgb = b.betty_hypergrad_neumann(w, lam, wl.K, big_alpha)
         errs["neumann_big_alpha"] = rel_l2(host(hgb), orc.hypergrad_neumann(prob, w64, lam64, wl.K, big_alpha))
 
+    # the best-response product on an arbitrary vector (the upper gradient is the special case above)
+    # (the vector is gradient-shaped, as in a chain of problems: the oracle's lower gradient, rounded to fp32)
+    u = g_ref.astype(np.float32)
+    br = b.betty_best_response_neumann(w, lam, dev(u), wl.K, wl.alpha)
+    errs["best_response"] = rel_l2(host(br), orc.best_response_neumann(prob, w64, lam64, u.astype(np.float64), wl.K, wl.alpha))
+    br0 = b.betty_best_response_neumann(w, lam, dev(u), 0, wl.alpha)
+    errs["best_response_K0"] = rel_l2(host(br0), orc.best_response_neumann(prob, w64, lam64, u.astype(np.float64), 0, wl.alpha))
+
     hc = b.betty_hypergrad_cg(w, lam, 3)
     errs["cg"] = rel_l2(host(hc), orc.hypergrad_cg(prob, w64, lam64, 3))
 
@@ -101,6 +109,8 @@ TINY = [
     dict(kind="l2", act="gelu", loss="mse", dims=(4, 5, 2)),
     dict(kind="reweight", act="gelu", loss="ce"),
     dict(kind="reweight", act="relu", loss="ce", dims=(6, 5, 4), batch=9),
+    dict(kind="proximal", act="gelu", loss="ce", prox_rho=0.3),
+    dict(kind="proximal", act="gelu", loss="mse", dims=(6, 5, 4), batch=9, prox_rho=0.1, prox_skip_last=True),
 ]
 
 
@@ -111,7 +121,7 @@ def test_tiny_fp32(cfg):
     run_all(wl, fd=wl.act != "relu", big_alpha=0.5)
 
 
-@pytest.mark.parametrize("cfg", [TINY[0], TINY[4], TINY[5]])
+@pytest.mark.parametrize("cfg", [TINY[0], TINY[4], TINY[5], TINY[6]])
 def test_tiny_bf16(cfg):
     wl = wk.tiny(prec="bf16", **cfg)
     run_all(wl, fd=wl.act != "relu")
@@ -121,6 +131,7 @@ def test_tiny_bf16(cfg):
     dict(kind="l2", act="gelu", loss="ce", dims=(300, 200, 150, 10), batch=130),
     dict(kind="reweight", act="gelu", loss="ce", dims=(257, 129, 33), batch=200, hidden=100),
     dict(kind="l2", act="relu", loss="ce", dims=(130, 260, 7), batch=70),
+    dict(kind="proximal", act="gelu", loss="ce", dims=(200, 140, 130, 9), batch=150, prox_rho=0.02, prox_skip_last=True),
 ])
 @pytest.mark.parametrize("prec", ["fp32", "bf16"])
 def test_ragged_multi_tile(cfg, prec):
@@ -282,7 +293,8 @@ def test_single_layer_softmax_regression():
     run_all(wl)
 
 
-@pytest.mark.parametrize("kind,prec,tol", [("l2", "fp32", 1e-4), ("reweight", "fp32", 1e-4), ("l2", "bf16", 2e-2)])
+@pytest.mark.parametrize("kind,prec,tol", [("l2", "fp32", 1e-4), ("reweight", "fp32", 1e-4), ("l2", "bf16", 2e-2),
+                                           ("proximal", "fp32", 1e-4)])
 def test_bilevel_steps_follow_the_oracle(kind, prec, tol):
     """Unrolled lower SGD steps, Neumann hypergradient at the unrolled w, Adam step on lambda:
     three outer steps of two inner steps each, every state vector against the oracle."""
@@ -322,3 +334,80 @@ def test_bilevel_steps_follow_the_oracle(kind, prec, tol):
         b.betty_lower_sgd_step(w, lam, w, lr_w, mu)
     assert e.value.status == binding.EINVAL
     b.close()
+
+
+# ---------------------------------------------------------------- three-level chain (Sec. 4.3)
+
+def run_chain3(pre_wl, ft_wl, K_pre, a_pre, K_ft, a_ft, tol):
+    pre, ft = oracle_problem(pre_wl), oracle_problem(ft_wl)
+    bp, bf = binding.from_workload(pre_wl), binding.from_workload(ft_wl)
+    w, theta, v = dev(pre_wl.w), dev(pre_wl.lam), dev(ft_wl.w)
+    w64, th64, v64 = (x.astype(np.float64) for x in (pre_wl.w, pre_wl.lam, ft_wl.w))
+    got = bp.betty_hypergrad_chain3(bf, w, theta, v, K_pre, a_pre, K_ft, a_ft)
+    ref = orc.hypergrad_chain3(pre, ft, w64, th64, v64, K_pre, a_pre, K_ft, a_ft)
+    err = rel_l2(host(got), ref)
+    # the same product composed by the caller from the two single-level calls
+    u = bf.betty_hypergrad_neumann(v, w, K_ft, a_ft)
+    u_ref = orc.hypergrad_neumann(ft, v64, w64, K_ft, a_ft)
+    err_u = rel_l2(host(u), u_ref)
+    got2 = bp.betty_best_response_neumann(w, theta, u, K_pre, a_pre)
+    torch.cuda.synchronize()
+    print(pre_wl.name, f"chain3 {err:.2e} finetune factor {err_u:.2e}", flush=True)
+    assert torch.equal(got, got2)
+    assert err < tol and err_u < tol, (err, err_u)
+    got3 = bp.betty_hypergrad_chain3(bf, w, theta, v, K_pre, a_pre, K_ft, a_ft)
+    torch.cuda.synchronize()
+    assert torch.equal(got, got3)
+    bp.close()
+    bf.close()
+
+
+@pytest.mark.parametrize("act,skip", [("gelu", True), ("relu", False)])
+def test_chain3_tiny_fp32(act, skip):
+    pre_wl, ft_wl = wk.chain3(seed=3, act=act, skip_last=skip)
+    run_chain3(pre_wl, ft_wl, 4, 0.06, 3, 0.09, 1e-4)
+    run_chain3(pre_wl, ft_wl, 0, 0.06, 0, 0.09, 1e-4)
+
+
+@pytest.mark.parametrize("prec", ["fp32", "bf16"])
+def test_chain3_ragged_multi_tile(prec):
+    pre_wl, ft_wl = wk.chain3(seed=1, dims=(300, 200, 150, 10), act="gelu", prec=prec, batch=130, hidden=100,
+                              rho=0.01, K=3, alpha=0.05)
+    run_chain3(pre_wl, ft_wl, 3, 0.05, 2, 0.05, TOL[prec])
+
+
+def test_chain3_config3_shape_bf16():
+    """The chain at the shape of the reweighting benchmark configuration (1024-512-512-10, batch 256)."""
+    pre_wl, ft_wl = wk.chain3(seed=0, dims=(1024, 512, 512, 10), act="relu", prec="bf16", batch=256, hidden=100,
+                              rho=0.007, noise_p=0.4, sigma=2.0, K=3, alpha=0.01)
+    run_chain3(pre_wl, ft_wl, 3, 0.01, 3, 0.01, TOL["bf16"])
+
+
+def test_chain3_with_l2_pretraining_level():
+    """The pretraining level may carry any upper variable the library knows: here per-parameter decay."""
+    pre_wl = wk.tiny(kind="l2", act="gelu", dims=(12, 9, 4), batch=20, seed=5)
+    _, ft_wl = wk.chain3(seed=5, dims=(12, 9, 4), act="gelu", batch=20)
+    ft_wl.lam = pre_wl.w.copy()
+    run_chain3(pre_wl, ft_wl, 3, 0.05, 3, 0.05, 1e-4)
+
+
+def test_chain3_argument_errors():
+    pre_wl, ft_wl = wk.chain3(seed=3)
+    bp, bf = binding.from_workload(pre_wl), binding.from_workload(ft_wl)
+    w, theta, v = dev(pre_wl.w), dev(pre_wl.lam), dev(ft_wl.w)
+    out = torch.full((bp.n_hyper,), 7.0, device="cuda")
+    with pytest.raises(binding.BettyError) as e:
+        bp.betty_hypergrad_chain3(bp, w, theta, v, 2, 0.05, 2, 0.05, out=out)      # not a proximal handle
+    assert e.value.status == binding.EINVAL
+    with pytest.raises(binding.BettyError) as e:
+        bp.betty_hypergrad_chain3(bf, w, theta, v, 2, 0.05, -1, 0.05, out=out)
+    assert e.value.status == binding.EINVAL
+    other = binding.from_workload(wk.tiny(kind="proximal", dims=(5, 4, 3, 3)))
+    with pytest.raises(binding.BettyError) as e:
+        bp.betty_hypergrad_chain3(other, w, theta, v, 2, 0.05, 2, 0.05, out=out)   # different parameter count
+    assert e.value.status == binding.ESHAPE
+    with pytest.raises(binding.BettyError) as e:
+        bp.betty_best_response_neumann(w, theta, w, 2, 0.05, out=w[:bp.n_hyper])   # output overlaps an input
+    assert e.value.status == binding.EINVAL
+    torch.cuda.synchronize()
+    assert (out == 7.0).all()
