@@ -98,14 +98,18 @@ def main():
     K, alpha = wl.K, wl.alpha
 
     def timed(fn, steps, warmup):
-        for _ in range(warmup):
-            fn()
+        # the calls are issued with the handle's stream current, so the binding adds no
+        # cross-stream ordering events around them
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / steps
+        with torch.cuda.stream(b.stream):
+            for _ in range(warmup):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / steps
 
     t_step = timed(lambda: b.betty_hypergrad_neumann(w, lam, K, alpha, out=out), args.steps, args.warmup)
     if args.only_neumann:
@@ -131,6 +135,19 @@ def main():
         b.betty_upper_adam_step(lam_work, out, am, av, counter[0], 1e-5)
     t_bilevel = timed(bilevel, n_side, 5)
 
+    # the three-level chain (reweight -> pretrain -> finetune) on the same architecture and batch sizes
+    t_chain = None
+    if wl.d < 5e7:
+        pre_wl, ft_wl = wk.chain3(seed=0, dims=wl.dims, act=wl.act, prec=wl.prec, batch=wl.X_tr.shape[0],
+                                  hidden=100, rho=0.007, sigma=2.0, K=K, alpha=alpha)
+        bp = binding.from_workload(pre_wl, stream=b.stream)
+        bf = binding.from_workload(ft_wl, stream=b.stream)
+        cw, cth, cv = (torch.as_tensor(x).cuda() for x in (pre_wl.w, pre_wl.lam, ft_wl.w))
+        cout = torch.empty(bp.n_hyper, dtype=torch.float32, device="cuda")
+        t_chain = timed(lambda: bp.betty_hypergrad_chain3(bf, cw, cth, cv, K, alpha, K, alpha, out=cout), n_side, 5)
+        bp.close()
+        bf.close()
+
     B = wl.X_tr.shape[0]
     grad_flops, hvp_flops = algorithmic_flops(wl.dims, B)
     t_hvp = (t_step - t_k0) / K if K > 0 else float("nan")
@@ -138,9 +155,10 @@ def main():
     # per-kernel durations from HIP events around every launch of a few extra steps
     b.profile(True)
     n_prof = 5
-    for _ in range(n_prof):
-        b.betty_hypergrad_neumann(w, lam, K, alpha, out=out)
-    recs = b.profile_records()
+    with torch.cuda.stream(b.stream):
+        for _ in range(n_prof):
+            b.betty_hypergrad_neumann(w, lam, K, alpha, out=out)
+        recs = b.profile_records()
     b.profile(False)
     by_kind = {}
     for kind, ms, flops, nbytes in recs:
@@ -193,6 +211,10 @@ def main():
         "fd_hypergradients_per_s": (1.0 / t_fd) if t_fd else None,
         "bilevel_upper_steps_per_s": {"value": 1.0 / t_bilevel,
                                       "step": "1 lower momentum-SGD step + Neumann hypergradient + Adam step on lambda"},
+        "chain3_hypergradients_per_s": None if t_chain is None else {
+            "value": 1.0 / t_chain,
+            "step": f"three-level chain on the same architecture: Neumann K={K} best-response product on the "
+                    "proximal finetuning problem, then on the reweighting pretraining problem"},
     }
 
     if not args.no_cpu_baseline:

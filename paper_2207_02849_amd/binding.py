@@ -131,13 +131,31 @@ class Betty:
         self.batch_train, self.batch_val = batch_train, batch_val
         nbytes = self.lib.betty_workspace_bytes(self.h)
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
-        self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        # The library captures repeated calls into HIP graphs and overlaps launches on a second stream;
+        # neither is possible on the legacy default stream, so without an explicit stream the handle
+        # gets one of its own (default priority).  Whenever the handle's stream is not the caller's
+        # current torch stream, every call is ordered against that stream with events, before and after.
+        # Handles that work together (betty_hypergrad_chain3) must share a stream: pass the first one's.
+        self.stream = torch.cuda.Stream(self.device) if stream is None else stream
+        cur = torch.cuda.current_stream(self.device)
+        if cur.cuda_stream != self.stream.cuda_stream:
+            self.stream.wait_stream(cur)
         self._check(self.lib.betty_bind(self.h, self.workspace.data_ptr(), nbytes, self.stream.cuda_stream))
         self._keep = []
 
     def _check(self, st):
         if st != OK:
             raise BettyError(st, self.lib.betty_last_error(self.h).decode())
+
+    def _call(self, fn, *args):
+        cur = torch.cuda.current_stream(self.device)
+        foreign = cur.cuda_stream != self.stream.cuda_stream
+        if foreign:
+            self.stream.wait_stream(cur)
+        st = fn(self.h, *args)
+        if foreign:
+            cur.wait_stream(self.stream)
+        self._check(st)
 
     def close(self):
         if getattr(self, "h", None) is not None and self.h.value:
@@ -161,88 +179,88 @@ class Betty:
         va = Batch(_ptr(X_val, torch.float32, self.batch_val * n0), _ptr(y_val, torch.int32, self.batch_val) if y_val is not None else None,
                    _ptr(t_val, torch.float32, self.batch_val * nL) if t_val is not None else None)
         self._keep = [X_tr, X_val, y_tr, y_val, t_tr, t_val]
-        self._check(self.lib.betty_set_batches(self.h, tr, va))
+        self._call(self.lib.betty_set_batches, tr, va)
 
     # ---- the calls of include/betty_hip.h, same names
     def betty_lower_grad(self, w, lam, want_loss=False):
         g = self._vec(self.d)
         loss = self._vec(1) if want_loss else None
-        self._check(self.lib.betty_lower_grad(self.h, _ptr(w, torch.float32, self.d), _ptr(lam, torch.float32, self.n_hyper),
-                                              g.data_ptr(), _ptr(loss)))
+        self._call(self.lib.betty_lower_grad, _ptr(w, torch.float32, self.d), _ptr(lam, torch.float32, self.n_hyper),
+                                              g.data_ptr(), _ptr(loss))
         return (g, loss) if want_loss else g
 
     def betty_upper_grad(self, w, want_loss=False):
         g = self._vec(self.d)
         loss = self._vec(1) if want_loss else None
-        self._check(self.lib.betty_upper_grad(self.h, _ptr(w, torch.float32, self.d), g.data_ptr(), _ptr(loss)))
+        self._call(self.lib.betty_upper_grad, _ptr(w, torch.float32, self.d), g.data_ptr(), _ptr(loss))
         return (g, loss) if want_loss else g
 
     def betty_hvp(self, w, lam, v, out=None):
         Hv = out if out is not None else self._vec(self.d)
-        self._check(self.lib.betty_hvp(self.h, _ptr(w, torch.float32, self.d), _ptr(lam, torch.float32, self.n_hyper),
-                                       _ptr(v, torch.float32, self.d), _ptr(Hv, torch.float32, self.d)))
+        self._call(self.lib.betty_hvp, _ptr(w, torch.float32, self.d), _ptr(lam, torch.float32, self.n_hyper),
+                                       _ptr(v, torch.float32, self.d), _ptr(Hv, torch.float32, self.d))
         return Hv
 
     def betty_mixed_vjp(self, w, lam, q, out=None):
         o = out if out is not None else self._vec(self.n_hyper)
-        self._check(self.lib.betty_mixed_vjp(self.h, _ptr(w, torch.float32, self.d), _ptr(lam, torch.float32, self.n_hyper),
-                                             _ptr(q, torch.float32, self.d), _ptr(o, torch.float32, self.n_hyper)))
+        self._call(self.lib.betty_mixed_vjp, _ptr(w, torch.float32, self.d), _ptr(lam, torch.float32, self.n_hyper),
+                                             _ptr(q, torch.float32, self.d), _ptr(o, torch.float32, self.n_hyper))
         return o
 
     def betty_hypergrad_neumann(self, w, lam, K, alpha, out=None):
         o = out if out is not None else self._vec(self.n_hyper)
-        self._check(self.lib.betty_hypergrad_neumann(self.h, _ptr(w, torch.float32, self.d),
+        self._call(self.lib.betty_hypergrad_neumann, _ptr(w, torch.float32, self.d),
                                                      _ptr(lam, torch.float32, self.n_hyper), int(K), float(alpha),
-                                                     _ptr(o, torch.float32, self.n_hyper)))
+                                                     _ptr(o, torch.float32, self.n_hyper))
         return o
 
     def betty_hypergrad_fd(self, w, lam, K, alpha, eps_scale=0.01, out=None):
         o = out if out is not None else self._vec(self.n_hyper)
-        self._check(self.lib.betty_hypergrad_fd(self.h, _ptr(w, torch.float32, self.d),
+        self._call(self.lib.betty_hypergrad_fd, _ptr(w, torch.float32, self.d),
                                                 _ptr(lam, torch.float32, self.n_hyper), int(K), float(alpha),
-                                                float(eps_scale), _ptr(o, torch.float32, self.n_hyper)))
+                                                float(eps_scale), _ptr(o, torch.float32, self.n_hyper))
         return o
 
     def betty_hypergrad_cg(self, w, lam, K, out=None):
         o = out if out is not None else self._vec(self.n_hyper)
-        self._check(self.lib.betty_hypergrad_cg(self.h, _ptr(w, torch.float32, self.d),
+        self._call(self.lib.betty_hypergrad_cg, _ptr(w, torch.float32, self.d),
                                                 _ptr(lam, torch.float32, self.n_hyper), int(K),
-                                                _ptr(o, torch.float32, self.n_hyper)))
+                                                _ptr(o, torch.float32, self.n_hyper))
         return o
 
     def betty_best_response_neumann(self, w, lam, u, K, alpha, out=None):
         o = out if out is not None else self._vec(self.n_hyper)
-        self._check(self.lib.betty_best_response_neumann(self.h, _ptr(w, torch.float32, self.d),
+        self._call(self.lib.betty_best_response_neumann, _ptr(w, torch.float32, self.d),
                                                          _ptr(lam, torch.float32, self.n_hyper),
                                                          _ptr(u, torch.float32, self.d), int(K), float(alpha),
-                                                         _ptr(o, torch.float32, self.n_hyper)))
+                                                         _ptr(o, torch.float32, self.n_hyper))
         return o
 
     def betty_hypergrad_chain3(self, finetune: "Betty", w, theta, v, K_pretrain, alpha_pretrain, K_finetune,
                                alpha_finetune, out=None):
         """self is the pretraining problem's handle, `finetune` the proximal one."""
         o = out if out is not None else self._vec(self.n_hyper)
-        self._check(self.lib.betty_hypergrad_chain3(self.h, finetune.h, _ptr(w, torch.float32, self.d),
+        self._call(self.lib.betty_hypergrad_chain3, finetune.h, _ptr(w, torch.float32, self.d),
                                                     _ptr(theta, torch.float32, self.n_hyper),
                                                     _ptr(v, torch.float32, self.d), int(K_pretrain),
                                                     float(alpha_pretrain), int(K_finetune), float(alpha_finetune),
-                                                    _ptr(o, torch.float32, self.n_hyper)))
+                                                    _ptr(o, torch.float32, self.n_hyper))
         return o
 
     def betty_lower_sgd_step(self, w, lam, momentum, lr, mu, weight_decay=0.0, want_loss=False):
         loss = self._vec(1) if want_loss else None
-        self._check(self.lib.betty_lower_sgd_step(self.h, _ptr(w, torch.float32, self.d),
+        self._call(self.lib.betty_lower_sgd_step, _ptr(w, torch.float32, self.d),
                                                   _ptr(lam, torch.float32, self.n_hyper),
                                                   _ptr(momentum, torch.float32, self.d), float(lr), float(mu),
-                                                  float(weight_decay), _ptr(loss)))
+                                                  float(weight_decay), _ptr(loss))
         return loss
 
     def betty_upper_adam_step(self, lam, dlam, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8):
-        self._check(self.lib.betty_upper_adam_step(self.h, _ptr(lam, torch.float32, self.n_hyper),
+        self._call(self.lib.betty_upper_adam_step, _ptr(lam, torch.float32, self.n_hyper),
                                                    _ptr(dlam, torch.float32, self.n_hyper),
                                                    _ptr(m, torch.float32, self.n_hyper),
                                                    _ptr(v, torch.float32, self.n_hyper), int(t), float(lr),
-                                                   float(beta1), float(beta2), float(eps)))
+                                                   float(beta1), float(beta2), float(eps))
 
     def betty_apply_label_noise(self, y, words, alt, p, want_mask=True):
         n = y.numel()
@@ -250,8 +268,8 @@ class Betty:
             raise ValueError("words must hold 32-bit values")
         out = torch.empty(n, dtype=torch.int32, device=self.device)
         mask = torch.empty(n, dtype=torch.uint8, device=self.device) if want_mask else None
-        self._check(self.lib.betty_apply_label_noise(self.h, _ptr(y, torch.int32), _ptr(words, None, n),
-                                                     _ptr(alt, torch.int32, n), float(p), n, out.data_ptr(), _ptr(mask)))
+        self._call(self.lib.betty_apply_label_noise, _ptr(y, torch.int32), _ptr(words, None, n),
+                                                     _ptr(alt, torch.int32, n), float(p), n, out.data_ptr(), _ptr(mask))
         return out, mask
 
     # ---- per-kernel timing
@@ -267,11 +285,11 @@ class Betty:
         return out
 
 
-def from_workload(wl, device="cuda:0") -> "Betty":
+def from_workload(wl, device="cuda:0", stream=None) -> "Betty":
     """Creates a handle for a seeded workload and uploads its batches."""
     b = Betty(wl.dims, act=wl.act, loss=wl.loss, hp=wl.hp, prec=wl.prec, has_bias=wl.has_bias,
               batch_train=wl.X_tr.shape[0], batch_val=wl.X_val.shape[0], wnet_hidden=wl.wnet_hidden,
-              prox_rho=wl.prox_rho, prox_skip_last=wl.prox_skip_last, device=device)
+              prox_rho=wl.prox_rho, prox_skip_last=wl.prox_skip_last, device=device, stream=stream)
     dev = b.device
 
     def up(a, dt):

@@ -340,7 +340,8 @@ def test_bilevel_steps_follow_the_oracle(kind, prec, tol):
 
 def run_chain3(pre_wl, ft_wl, K_pre, a_pre, K_ft, a_ft, tol):
     pre, ft = oracle_problem(pre_wl), oracle_problem(ft_wl)
-    bp, bf = binding.from_workload(pre_wl), binding.from_workload(ft_wl)
+    bp = binding.from_workload(pre_wl)
+    bf = binding.from_workload(ft_wl, stream=bp.stream)
     w, theta, v = dev(pre_wl.w), dev(pre_wl.lam), dev(ft_wl.w)
     w64, th64, v64 = (x.astype(np.float64) for x in (pre_wl.w, pre_wl.lam, ft_wl.w))
     got = bp.betty_hypergrad_chain3(bf, w, theta, v, K_pre, a_pre, K_ft, a_ft)
@@ -393,7 +394,8 @@ def test_chain3_with_l2_pretraining_level():
 
 def test_chain3_argument_errors():
     pre_wl, ft_wl = wk.chain3(seed=3)
-    bp, bf = binding.from_workload(pre_wl), binding.from_workload(ft_wl)
+    bp = binding.from_workload(pre_wl)
+    bf = binding.from_workload(ft_wl, stream=bp.stream)
     w, theta, v = dev(pre_wl.w), dev(pre_wl.lam), dev(ft_wl.w)
     out = torch.full((bp.n_hyper,), 7.0, device="cuda")
     with pytest.raises(binding.BettyError) as e:
@@ -402,12 +404,44 @@ def test_chain3_argument_errors():
     with pytest.raises(binding.BettyError) as e:
         bp.betty_hypergrad_chain3(bf, w, theta, v, 2, 0.05, -1, 0.05, out=out)
     assert e.value.status == binding.EINVAL
-    other = binding.from_workload(wk.tiny(kind="proximal", dims=(5, 4, 3, 3)))
+    other = binding.from_workload(wk.tiny(kind="proximal", dims=(5, 4, 3, 3)), stream=bp.stream)
     with pytest.raises(binding.BettyError) as e:
         bp.betty_hypergrad_chain3(other, w, theta, v, 2, 0.05, 2, 0.05, out=out)   # different parameter count
     assert e.value.status == binding.ESHAPE
+    lone = binding.from_workload(ft_wl)                                            # a stream of its own
+    with pytest.raises(binding.BettyError) as e:
+        bp.betty_hypergrad_chain3(lone, w, theta, v, 2, 0.05, 2, 0.05, out=out)
+    assert e.value.status == binding.EINVAL
     with pytest.raises(binding.BettyError) as e:
         bp.betty_best_response_neumann(w, theta, w, 2, 0.05, out=w[:bp.n_hyper])   # output overlaps an input
     assert e.value.status == binding.EINVAL
     torch.cuda.synchronize()
     assert (out == 7.0).all()
+
+
+@pytest.mark.parametrize("kind", ["l2", "reweight"])
+def test_pipelined_recurrence_is_bit_identical_to_the_serial_one(kind, monkeypatch):
+    """Large models run each layer's weight-gradient launch on a second stream while the R-backward
+    chain continues; forced on here for a small model: same kernels on the same data, so the
+    result must not change by a bit, directly launched or replayed from the captured graph."""
+    wl = wk.tiny(kind=kind, act="gelu", dims=(300, 200, 150, 10), batch=130, prec="bf16", hidden=100)
+    w, lam = dev(wl.w), dev(wl.lam)
+    monkeypatch.setenv("BETTY_TUNE", "pipe=0")
+    b0 = binding.from_workload(wl)
+    ref = b0.betty_hypergrad_neumann(w, lam, 4, 0.05).clone()
+    ref_odd = b0.betty_hypergrad_neumann(w, lam, 3, 0.05).clone()
+    b0.close()
+    monkeypatch.setenv("BETTY_TUNE", "pipe=1")
+    b1 = binding.from_workload(wl)
+    out = torch.empty(b1.n_hyper, device="cuda")
+    for rep in range(4):                      # direct, capture, two replays
+        out.zero_()
+        b1.betty_hypergrad_neumann(w, lam, 4, 0.05, out=out)
+        Hv = b1.betty_hvp(w, lam, w)          # unrelated direct work in between
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), rep
+    got_odd = b1.betty_hypergrad_neumann(w, lam, 3, 0.05)
+    torch.cuda.synchronize()
+    assert torch.equal(got_odd, ref_odd)
+    assert rel_l2(host(out), orc.hypergrad_neumann(oracle_problem(wl), wl.w, wl.lam, 4, 0.05)) < 2e-2
+    b1.close()
