@@ -466,7 +466,16 @@ void wgrad_batch(betty_handle h, OperandSet& os, int side, bool rop, const Wgrad
       const LayerInfo& li = h->layers[l0 + i - 1];
       params += (double)li.n_in * li.n_out + (h->desc.has_bias ? li.n_out : 0);
     }
-    launch_gemm_batch(h->ctx, os.elem, h->tune_wgrad_cfg, b, flops, 20.0 * params);
+    // algorithmic bytes per parameter of the epilogue's vector work (fp32 vectors 4 B each way,
+    // operand copies 2 x 2 B): Neumann step reads s, g (+ the diagonal), writes s and the copies
+    double per_param = 4.0;
+    if (k.mode == EPI_WGRAD_NEUMANN) per_param = 8.0 + 4.0 + (k.lam ? 4.0 : 0.0);
+    else if (k.mode == EPI_WGRAD_NEUMANN_L2) per_param = 16.0 + 4.0;
+    else if (k.mode == EPI_WGRAD_SGD) per_param = 16.0 + (k.lam ? 4.0 : 0.0);
+    else if (k.mode == EPI_WGRAD_INIT) per_param = k.p ? 8.0 : 4.0;
+    else if (k.lam) per_param = 12.0;
+    if (k.copies) per_param += 4.0;
+    launch_gemm_batch(h->ctx, os.elem, h->tune_wgrad_cfg, b, flops, per_param * params);
   }
 }
 
@@ -717,47 +726,51 @@ static betty_status check_hyper_args(betty_handle h, const float* w, const float
 
 // out = (dw* / dlambda) u by the K-step Neumann series and the mixed VJP; u = grad_w L_U(w) on the
 // validation batch when u_or_null is null.  Only enqueues launches on the handle's stream.
+// The partial sum is carried in nested form, s <- g + (I - alpha H) s from s = g: after K steps
+// s = sum_{j<=K} (I - alpha H)^j g, with one parameter-sized state vector to read and write per step.
 static void neumann_seq(betty_handle h, const float* w, const float* lambda, const float* u_or_null, int K,
                         float alpha, float* out) {
   OperandSet& os = h->sets[0];
   const bool l2 = h->desc.hp == BETTY_HP_L2_DECAY, rw = h->desc.hp == BETTY_HP_REWEIGHT_NET;
   const float* dl = diag_log(h, lambda);
-  float* v = h->f(h->vec_v); float* p = h->f(h->vec_p);
+  float* s = h->f(h->vec_p);
+  const float* g = u_or_null;
   const bool need_lower = K > 0 || rw;      // forward/backward cache of the train batch
   make_weight_operands(h, os, w);
   if (u_or_null) {
     if (need_lower) prepare_lower(h, os, w, lambda);
-    launch_scale_copy(h->ctx, u_or_null, 1.f, v, h->d);
-    launch_scale_copy(h->ctx, u_or_null, 1.f, p, h->d);
     if (K > 0) make_shadows(h, os, u_or_null, 1.f, &os.Vn, &os.Vt);
   } else {
-    // g = grad_w L_U lands directly in v and p, with the operand copies of v for the first product
-    WgradSink init{EPI_WGRAD_INIT, nullptr, nullptr, nullptr, v, p, 0.f, K > 0};
+    // g = grad_w L_U lands in vec_v, with its operand copies for the first product
+    WgradSink init{EPI_WGRAD_INIT, nullptr, nullptr, nullptr, h->f(h->vec_v), nullptr, 0.f, K > 0};
     upper_grad_seq(h, os, w, lambda, need_lower, init, nullptr);
+    g = h->f(h->vec_v);
   }
+  const float* s_cur = g;                   // s_0 = g
   for (int k = 0; k < K; ++k) {
-    // v <- v - alpha (H v), p <- p + v fused into the weight-gradient epilogues of the product;
-    // for L2 decay the last step also applies the mixed VJP, so only d(lambda) is written
+    // the step is fused into the weight-gradient epilogues of the product; for L2 decay the last
+    // step also applies the mixed VJP, so only d(lambda) is written.
     // With the second stream, layer l's launch runs while the R-backward chain is still reading
     // this product's direction copies of the layers below, so the new copies go to the other set.
     const bool last = k + 1 == K;
     const bool pipe = h->use_pipeline && h->side_stream && h->L >= 2;
     if (last && l2) {
-      WgradSink fin{EPI_WGRAD_NEUMANN_L2, out, lambda, w, v, p, alpha, false};
-      hvp_cached(h, os, v, fin, pipe);
+      WgradSink fin{EPI_WGRAD_NEUMANN_L2, out, lambda, w, const_cast<float*>(g), const_cast<float*>(s_cur), alpha, false};
+      hvp_cached(h, os, s_cur, fin, pipe);
     } else {
-      WgradSink step{EPI_WGRAD_NEUMANN, nullptr, dl, nullptr, v, p, alpha, !last};
+      WgradSink step{EPI_WGRAD_NEUMANN, nullptr, dl, s_cur, const_cast<float*>(g), s, alpha, !last};
       step.second_set = pipe;
-      hvp_cached(h, os, v, step, pipe);
+      hvp_cached(h, os, s_cur, step, pipe);
       if (pipe && !last) { std::swap(os.Vn, os.Vn2); std::swap(os.Vt, os.Vt2); }
     }
+    s_cur = s;
   }
   if (l2) {
-    if (K == 0) launch_mixed_l2(h->ctx, lambda, w, p, alpha, out, h->d);
+    if (K == 0) launch_mixed_l2(h->ctx, lambda, w, s_cur, alpha, out, h->d);
   } else if (rw) {
-    mixed_reweight_seq(h, os, lambda, p, alpha, out);
+    mixed_reweight_seq(h, os, lambda, s_cur, alpha, out);
   } else {
-    launch_mixed_prox(h->ctx, h->f(h->logrho), p, alpha, out, h->d);
+    launch_mixed_prox(h->ctx, h->f(h->logrho), s_cur, alpha, out, h->d);
   }
 }
 

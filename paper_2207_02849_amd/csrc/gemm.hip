@@ -121,14 +121,14 @@ __device__ __forceinline__ void epi_prefetch(const Epilogue& e, int M, int N, in
       R.a[k] = (ok && e.lam) ? e.lam[o] : 0.f;
       R.b[k] = (ok && e.lam) ? e.x[o] : 0.f;
     } else if constexpr (MODE == EPI_WGRAD_NEUMANN) {
-      R.a[k] = ok ? e.v[o] : 0.f;
-      R.b[k] = ok ? e.p[o] : 0.f;
+      R.a[k] = ok ? e.x[o] : 0.f;                         // s: the partial sum so far
+      R.b[k] = ok ? e.v[o] : 0.f;                         // g: the vector the series is applied to
       R.c[k] = (ok && e.lam) ? e.lam[o] : 0.f;
     } else if constexpr (MODE == EPI_WGRAD_NEUMANN_L2) {
-      R.a[k] = ok ? e.v[o] : 0.f;
-      R.b[k] = ok ? e.p[o] : 0.f;
+      R.a[k] = ok ? e.p[o] : 0.f;                         // s
+      R.b[k] = ok ? e.v[o] : 0.f;                         // g
       R.c[k] = ok ? e.lam[o] : 0.f;
-      R.d[k] = ok ? e.x[o] : 0.f;
+      R.d[k] = ok ? e.x[o] : 0.f;                         // w
     } else if constexpr (MODE == EPI_WGRAD_SGD) {
       R.a[k] = ok ? e.v[o] : 0.f;
       R.b[k] = ok ? e.p[o] : 0.f;
@@ -196,22 +196,22 @@ __device__ __forceinline__ void epi_finish(const Epilogue& e, int M, int N, int 
         if (ok[k]) e.C[of[k]] = acc[k];
     }
     return;
-  } else if constexpr (MODE == EPI_WGRAD_INIT) {       // v = p = acc ; operand copies of v
+  } else if constexpr (MODE == EPI_WGRAD_INIT) {       // v = acc (and p = acc if asked); operand copies
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
       val[k] = acc[k];
-      if (ok[k]) { e.v[of[k]] = acc[k]; e.p[of[k]] = acc[k]; }
+      if (ok[k]) { e.v[of[k]] = acc[k]; if (e.p) e.p[of[k]] = acc[k]; }
     }
-  } else if constexpr (MODE == EPI_WGRAD_NEUMANN) {    // Hv = acc (+ 2 e^lam v); v -= alpha Hv; p += v
+  } else if constexpr (MODE == EPI_WGRAD_NEUMANN) {    // Hs = acc (+ 2 e^lam s); s <- g + s - alpha Hs
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
-      float hv = acc[k];
-      if (e.lam) hv += 2.f * expf(R.c[k]) * R.a[k];
-      val[k] = R.a[k] - e.alpha * hv;
+      float hs = acc[k];
+      if (e.lam) hs += 2.f * expf(R.c[k]) * R.a[k];
+      val[k] = R.b[k] + (R.a[k] - e.alpha * hs);
     }
 #pragma unroll
     for (int k = 0; k < 16; ++k)
-      if (ok[k]) { e.v[of[k]] = val[k]; e.p[of[k]] = R.b[k] + val[k]; }
+      if (ok[k]) e.p[of[k]] = val[k];
   } else if constexpr (MODE == EPI_WGRAD_SGD) {          // lower optimiser step: momentum SGD in place
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
@@ -225,8 +225,8 @@ __device__ __forceinline__ void epi_finish(const Epilogue& e, int M, int N, int 
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
       const float el = 2.f * expf(R.c[k]);
-      const float vn = R.a[k] - e.alpha * (acc[k] + el * R.a[k]);
-      if (ok[k]) e.C[of[k]] = -el * R.d[k] * (e.alpha * (R.b[k] + vn));
+      const float sn = R.b[k] + (R.a[k] - e.alpha * (acc[k] + el * R.a[k]));
+      if (ok[k]) e.C[of[k]] = -el * R.d[k] * (e.alpha * sn);
     }
     return;
   } else {
@@ -281,15 +281,14 @@ __device__ void bias_rows(const BiasJob& j, int row) {
       break;
     }
     case EPI_WGRAD_INIT:
-      j.v[row] = acc; j.p[row] = acc;
+      j.v[row] = acc;
+      if (j.p) j.p[row] = acc;
       break;
     case EPI_WGRAD_NEUMANN: {
-      const float vo = j.v[row];
-      float hv = acc;
-      if (j.lam) hv += 2.f * expf(j.lam[row]) * vo;
-      const float vn = vo - j.alpha * hv;
-      j.v[row] = vn;
-      j.p[row] += vn;
+      const float so = j.x[row];
+      float hs = acc;
+      if (j.lam) hs += 2.f * expf(j.lam[row]) * so;
+      j.p[row] = j.v[row] + (so - j.alpha * hs);
       break;
     }
     case EPI_WGRAD_SGD: {
@@ -302,9 +301,9 @@ __device__ void bias_rows(const BiasJob& j, int row) {
       break;
     }
     case EPI_WGRAD_NEUMANN_L2: {
-      const float vo = j.v[row], el = 2.f * expf(j.lam[row]);
-      const float vn = vo - j.alpha * (acc + el * vo);
-      j.C[row] = -el * j.x[row] * (j.alpha * (j.p[row] + vn));
+      const float so = j.p[row], el = 2.f * expf(j.lam[row]);
+      const float sn = j.v[row] + (so - j.alpha * (acc + el * so));
+      j.C[row] = -el * j.x[row] * (j.alpha * sn);
       break;
     }
     default: break;

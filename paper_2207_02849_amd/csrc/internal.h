@@ -41,9 +41,13 @@ enum EpiMode {
   EPI_RFWD_LAST,         // f0 = acc + cbias
   EPI_RBWD,              // out = acc * dphi + e * Rz
   EPI_WGRAD,             // C = acc (+ 2 exp(lam) x)                       flat parameter layout
-  EPI_WGRAD_INIT,        // v = p = acc; out = operand copies of v
-  EPI_WGRAD_NEUMANN,     // Hv = acc (+ 2 exp(lam) v); v -= alpha Hv; p += v; out = copies of v
-  EPI_WGRAD_NEUMANN_L2,  // last step for L2 decay: same update in registers, C = -2 exp(lam) x (alpha p)
+  EPI_WGRAD_INIT,        // v = acc (and p = acc when p is given); out = operand copies
+  // One step of the Neumann partial sum in nested form, s_{j+1} = g + (I - alpha H) s_j with s_0 = g
+  // (the same sum_{i<=j} (I - alpha H)^i g as the term-by-term recurrence, one state vector instead
+  // of two): s is read from x, g from v;  Hs = acc (+ 2 exp(lam) s);  p = g + s - alpha Hs;  out =
+  // operand copies of the new s.
+  EPI_WGRAD_NEUMANN,
+  EPI_WGRAD_NEUMANN_L2,  // last step for L2 decay: s read from p, new s kept in registers, C = -2 exp(lam) x (alpha s)
   EPI_WGRAD_SGD          // g = acc (+ 2 exp(lam) p) + gamma p; v <- beta v + g; p <- p - alpha v  (p = w, v = momentum)
 };
 
