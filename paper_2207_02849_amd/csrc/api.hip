@@ -481,17 +481,26 @@ void wgrad_batch(betty_handle h, OperandSet& os, int side, bool rop, const Wgrad
 
 // R-forward along the direction whose operand copies are in os.Vt and whose fp32 flat form is
 // `vflat` (for the bias directions).  Leaves Rz_l (fp32) and Ra_l.
-void r_forward(betty_handle h, OperandSet& os, const float* vflat) {
+// With fuse_hessian (outputs of at most 32 columns) the last layer's epilogue applies the loss
+// Hessian and leaves R delta_L instead of Rz_L.
+void r_forward(betty_handle h, OperandSet& os, const float* vflat, bool fuse_hessian = false) {
   SideBuf& sb = os.side[0];
   const int L = h->L, B = sb.B, Bp = sb.Bp;
   for (int l = 1; l <= L; ++l) {
     const LayerInfo& li = h->layers[l - 1];
     const bool last = l == L;
     const void* a_prev = l == 1 ? h->at<void>(sb.X) : h->at<void>(sb.A[l - 1]);
-    Epilogue e = blank_epilogue(last ? EPI_RFWD_LAST : EPI_RFWD);
+    Epilogue e = blank_epilogue(last ? (fuse_hessian ? EPI_RFWD_LAST_HESS : EPI_RFWD_LAST) : EPI_RFWD);
     e.colvec = h->desc.has_bias ? vflat + li.b_off : nullptr;
     e.f0 = h->f(os.Rz[l]);
     e.ldf = li.n_out_p;
+    if (last && fuse_hessian) {
+      e.act = h->desc.loss;
+      e.dphi = h->desc.loss == BETTY_LOSS_SOFTMAX_CE ? h->f(sb.P) : nullptr;
+      e.e = h->f(sb.s);
+      e.out = h->at<void>(os.RD[l]); e.ld = li.n_out_p;
+      e.outT = h->at<void>(os.RDt[l]); e.ldT = Bp;
+    }
     if (!last) {
       e.dphi = h->f(sb.dphi[l]);
       e.out = h->at<void>(os.RA[l]); e.ld = li.n_out_p;
@@ -524,10 +533,12 @@ void hvp_cached(betty_handle h, OperandSet& os, const float* vflat, const WgradS
   SideBuf& sb = os.side[0];
   const int L = h->L, B = sb.B, Bp = sb.Bp;
   const bool pipe = pipelined && h->side_stream && L >= 2;
-  r_forward(h, os, vflat);
   const LayerInfo& lo = h->layers[L - 1];
-  launch_loss_hessian_rows(h->ctx, os.elem, h->desc.loss, h->f(sb.P), h->f(os.Rz[L]), lo.n_out_p, h->f(sb.s), B,
-                           lo.n_out, h->at<void>(os.RD[L]), lo.n_out_p, h->at<void>(os.RDt[L]), Bp);
+  const bool fused_hessian = lo.n_out <= 32;
+  r_forward(h, os, vflat, fused_hessian);
+  if (!fused_hessian)
+    launch_loss_hessian_rows(h->ctx, os.elem, h->desc.loss, h->f(sb.P), h->f(os.Rz[L]), lo.n_out_p, h->f(sb.s), B,
+                             lo.n_out, h->at<void>(os.RD[L]), lo.n_out_p, h->at<void>(os.RDt[L]), Bp);
   if (pipe) side_wgrad(h, os, sink, L);
   for (int l = L; l >= 2; --l) {
     const LayerInfo& li = h->layers[l - 1];

@@ -100,6 +100,19 @@ __device__ __forceinline__ int epi_offset(int rb, int k, long long ld, int col) 
 
 template <int MODE>
 __device__ __forceinline__ void epi_prefetch(const Epilogue& e, int M, int N, int rb, int col, EpiRegs& R) {
+  if constexpr (MODE == EPI_RFWD_LAST_HESS) {
+    // every lane of the block takes part in the row sums later: lanes outside the valid extent hold zeros
+    const bool colok = col < N;
+    R.colv = (colok && e.colvec) ? e.colvec[col] : 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const int row = rb + 8 * (k >> 2) + (k & 3);
+      const bool ok = colok && row < M;
+      R.a[k] = (ok && e.dphi) ? e.dphi[epi_offset(rb, k, e.ldf, col)] : 0.f;
+      R.b[k] = ok ? e.e[row] : 0.f;
+    }
+    return;
+  }
   if (col >= N || rb >= M) return;
   const long long ldx = MODE >= EPI_WGRAD ? e.ldc : e.ldf;
   if constexpr (MODE == EPI_FWD || MODE == EPI_FWD_LAST || MODE == EPI_RFWD || MODE == EPI_RFWD_LAST)
@@ -141,6 +154,28 @@ __device__ __forceinline__ void epi_prefetch(const Epilogue& e, int M, int N, in
 template <typename T, int MODE>
 __device__ __forceinline__ void epi_finish(const Epilogue& e, int M, int N, int rb, int col,
                                            const f32x16 acc, const EpiRegs& R) {
+  float val[16];
+  if constexpr (MODE == EPI_RFWD_LAST_HESS) {
+    // rows live across the 32 lanes of a half-wavefront (lane % 32 = column): butterfly sums
+    const bool colok = col < N;
+    float rz[16], dot[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      rz[k] = colok ? acc[k] + R.colv : 0.f;
+      dot[k] = R.a[k] * rz[k];
+    }
+    if (e.act == BETTY_LOSS_SOFTMAX_CE) {
+#pragma unroll
+      for (int o = 16; o > 0; o >>= 1)
+#pragma unroll
+        for (int k = 0; k < 16; ++k) dot[k] += __shfl_xor(dot[k], o, 64);
+#pragma unroll
+      for (int k = 0; k < 16; ++k) val[k] = R.b[k] * (R.a[k] * rz[k] - R.a[k] * dot[k]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < 16; ++k) val[k] = R.b[k] * 2.f * rz[k];
+    }
+  }
   if (col >= N || rb >= M) return;
   const long long ldx = MODE >= EPI_WGRAD ? e.ldc : e.ldf;
   bool ok[16];
@@ -150,8 +185,9 @@ __device__ __forceinline__ void epi_finish(const Epilogue& e, int M, int N, int 
     ok[k] = rb + 8 * (k >> 2) + (k & 3) < M;
     of[k] = epi_offset(rb, k, ldx, col);
   }
-  float val[16];
-  if constexpr (MODE == EPI_FWD) {
+  if constexpr (MODE == EPI_RFWD_LAST_HESS) {
+    // val is set; fall through to the operand copies
+  } else if constexpr (MODE == EPI_FWD) {
     float d1[16], d2[16];
 #pragma unroll
     for (int k = 0; k < 16; ++k) act_eval(e.act, acc[k] + R.colv, val[k], d1[k], d2[k]);
@@ -527,7 +563,7 @@ static void launch_chain_mode(int mode, int total, hipStream_t st, const GemmBat
   switch (mode) {
 #define BETTY_CASE(M_) case M_: launch_one<T, BT, WPG, KG, M_>(total, st, b, err); break;
     BETTY_CASE(EPI_FWD) BETTY_CASE(EPI_FWD_LAST) BETTY_CASE(EPI_BWD) BETTY_CASE(EPI_RFWD)
-    BETTY_CASE(EPI_RFWD_LAST) BETTY_CASE(EPI_RBWD)
+    BETTY_CASE(EPI_RFWD_LAST) BETTY_CASE(EPI_RBWD) BETTY_CASE(EPI_RFWD_LAST_HESS)
     default: err = hipErrorInvalidValue; break;
   }
 }

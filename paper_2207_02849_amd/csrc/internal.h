@@ -40,6 +40,12 @@ enum EpiMode {
   EPI_RFWD,              // f0 = rz = acc + cbias; out = dphi * rz
   EPI_RFWD_LAST,         // f0 = acc + cbias
   EPI_RBWD,              // out = acc * dphi + e * Rz
+  // Last layer of the R-forward with the loss Hessian applied in place (outputs of at most 32
+  // columns, so that one MFMA block holds whole rows): rz = acc + cbias;
+  // out = e[row] * (dphi .* rz - dphi * <dphi, rz>_row) for softmax cross-entropy (dphi = the
+  // softmax probabilities, e = the per-sample scale), out = 2 e[row] rz for the squared error;
+  // `act` carries the loss kind.
+  EPI_RFWD_LAST_HESS,
   EPI_WGRAD,             // C = acc (+ 2 exp(lam) x)                       flat parameter layout
   EPI_WGRAD_INIT,        // v = acc (and p = acc when p is given); out = operand copies
   // One step of the Neumann partial sum in nested form, s_{j+1} = g + (I - alpha H) s_j with s_0 = g
