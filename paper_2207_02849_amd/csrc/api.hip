@@ -218,13 +218,19 @@ const float* wnet_theta(betty_handle h, const float* lambda) {
 
 OperandSet& fd_operands(betty_handle h) { return h->sets[1].present ? h->sets[1] : h->sets[0]; }
 
-// Kernel configuration of an activation-shaped GEMM (M = batch): full 128-tiles when there are
-// enough of them to fill the chip, otherwise 64-tiles; K is split inside the workgroup when the
-// launch would still leave most compute units idle and K is long enough to share.
+// Kernel configuration of an activation-shaped GEMM (M = batch), from its tile count and the
+// number of k-tiles TT (thresholds from timings on this chip):
+//  * 128-tiles once there are enough of them to fill the chip several times over;
+//  * 32-tiles with an eight-way K split inside the workgroup when even 64-tiles would leave half
+//    the compute units idle (batch 256 against 1024-wide layers);
+//  * otherwise 64-tiles, K split four ways while the grid is still small.
+// Measured and dropped: 128-tiles with a two-way K split (2 x 512 x 4096 x 4096: 78 us against
+// 73 us for plain 64-tiles), and 64-tiles computed by one wavefront each over a quarter of K
+// (faster stand-alone, 54 against 62 us on 512 x 4096 x 8192, but 4 % slower with the real
+// epilogues, whose loads cannot be issued ahead of the k loop for four MFMA blocks per wavefront).
 int plan_chain(betty_handle h, Elem elem, int tiles128, int Ktot_p) {
   const int TT = Ktot_p / gemm_ktile_elems(elem);
   if (tiles128 >= h->tune_tile128_min) return GEMM_128x1;
-  if (tiles128 >= h->tune_tile128_min / 2 && TT >= 8) return GEMM_128x2;
   const int tiles64 = 4 * tiles128;
   if (tiles64 <= h->tune_target_blocks / 2 && TT >= 16) return GEMM_32x8;
   if (tiles64 < h->tune_target_blocks && TT >= 8) return GEMM_64x4;

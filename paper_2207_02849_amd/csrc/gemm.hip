@@ -590,7 +590,6 @@ static void launch_elem(int cfg, int mode, int total, hipStream_t st, const Gemm
   }
   switch (cfg) {
     case GEMM_128x1: launch_chain_mode<T, 128, 4, 1>(mode, total, st, b, err); break;
-    case GEMM_128x2: launch_chain_mode<T, 128, 4, 2>(mode, total, st, b, err); break;
     case GEMM_64x1: launch_chain_mode<T, 64, 4, 1>(mode, total, st, b, err); break;
     case GEMM_64x4: launch_chain_mode<T, 64, 4, 4>(mode, total, st, b, err); break;
     case GEMM_32x8: launch_chain_mode<T, 32, 1, 8>(mode, total, st, b, err); break;
@@ -599,8 +598,8 @@ static void launch_elem(int cfg, int mode, int total, hipStream_t st, const Gemm
 }
 
 int gemm_ktile_elems(Elem elem) { return GEMM_NCH * (elem == ELEM_BF16 ? 8 : 4); }
-int gemm_cfg_tile(int cfg) { return (cfg == GEMM_128x1 || cfg == GEMM_128x2) ? 128 : cfg == GEMM_32x8 ? 32 : 64; }
-static int gemm_cfg_waves(int cfg) { return cfg == GEMM_128x2 ? 8 : cfg == GEMM_64x4 ? 16 : cfg == GEMM_32x8 ? 8 : 4; }
+int gemm_cfg_tile(int cfg) { return cfg == GEMM_128x1 ? 128 : cfg == GEMM_32x8 ? 32 : 64; }
+static int gemm_cfg_waves(int cfg) { return cfg == GEMM_64x4 ? 16 : cfg == GEMM_32x8 ? 8 : 4; }
 
 void launch_gemm_batch(Ctx& ctx, Elem elem, int cfg, GemmBatch& b, double flops, double bytes) {
   const int bt = gemm_cfg_tile(cfg);

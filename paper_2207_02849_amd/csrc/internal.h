@@ -81,9 +81,9 @@ struct BiasJob {
 
 constexpr int MAX_PROBLEMS = 8;
 constexpr int GEMM_NCH = 8;              // 16-byte chunks per row of a k-tile
-// tile extent x number of K groups per workgroup
-// (32x8: one wavefront per K group, eight groups)
-enum { GEMM_128x1 = 0, GEMM_128x2 = 1, GEMM_64x1 = 2, GEMM_64x4 = 3, GEMM_32x8 = 4 };
+// tile extent x number of K groups per workgroup; a group is 2 x 2 wavefronts, except in 32x8
+// (32-tile, eight groups of one wavefront)
+enum { GEMM_128x1 = 0, GEMM_64x1 = 2, GEMM_64x4 = 3, GEMM_32x8 = 4 };
 
 struct GemmBatch {
   int n = 0, n_bias = 0, gemm_blocks = 0;
