@@ -619,20 +619,13 @@ void mixed_reweight_seq(betty_handle h, OperandSet& os, const float* lam, const 
   SideBuf& sb = os.side[0];
   const int L = h->L;
   const LayerInfo& lo = h->layers[L - 1];
-  // the direction is scale * qflat: scale once into a flat fp32 copy (its bias slices feed the
-  // R-forward epilogues), then make the transposed operand copies the R-forward needs
-  const float* qs = qflat;
-  if (scale != 1.f) {
-    float* tmp = h->f(h->vec_wpm);
-    launch_scale_copy(h->ctx, qflat, scale, tmp, h->d);
-    qs = tmp;
-  }
-  make_shadows(h, os, qs, 1.f, nullptr, &os.Vt);
-  r_forward(h, os, qs);
+  // c_i is linear in the direction, so the scale is applied once, to the final sum over samples
+  make_shadows(h, os, qflat, 1.f, nullptr, &os.Vt);
+  r_forward(h, os, qflat);
   launch_loss_directional_rows(h->ctx, h->desc.loss, h->f(sb.P), h->f(sb.ZL), h->batch[0].y,
                                h->batch[0].target, h->f(os.Rz[L]), lo.n_out_p, sb.B, lo.n_out, h->f(os.cvec));
   launch_wnet_theta_vjp(h->ctx, h->f(sb.ell), h->f(sb.omega), h->f(os.cvec), lam, h->desc.wnet_hidden, sb.B,
-                        1.0f / (float)sb.B, out);
+                        scale / (float)sb.B, out);
 }
 
 bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
