@@ -445,3 +445,28 @@ def test_pipelined_recurrence_is_bit_identical_to_the_serial_one(kind, monkeypat
     assert torch.equal(got_odd, ref_odd)
     assert rel_l2(host(out), orc.hypergrad_neumann(oracle_problem(wl), wl.w, wl.lam, 4, 0.05)) < 2e-2
     b1.close()
+
+
+def test_stored_tiny_hypergradients():
+    """The GPU results against expectations stored on disk (written by tests/golden/make_golden.py
+    from the oracle alone)."""
+    import json
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "tiny_hypergradients.json")
+    gold = json.load(open(path))
+    for case in gold["cases"]:
+        cfg = {k: (tuple(v) if isinstance(v, list) else v) for k, v in case["cfg"].items()}
+        wl = wk.tiny(**cfg)
+        b = binding.from_workload(wl)
+        w, lam = dev(wl.w), dev(wl.lam)
+        assert rel_l2(host(b.betty_hypergrad_neumann(w, lam, case["K"], case["alpha"])), case["neumann"]) < 1e-4
+        assert rel_l2(host(b.betty_hypergrad_fd(w, lam, case["K"], case["alpha"], case["eps_scale"])), case["fd"]) < 1e-4
+        assert rel_l2(host(b.betty_hypergrad_cg(w, lam, 3)), case["cg"]) < 1e-4
+        b.close()
+    c = gold["chain3"]
+    pre_wl, ft_wl = wk.chain3(seed=c["seed"], act="gelu", skip_last=True)
+    bp = binding.from_workload(pre_wl)
+    bf = binding.from_workload(ft_wl, stream=bp.stream)
+    got = bp.betty_hypergrad_chain3(bf, dev(pre_wl.w), dev(pre_wl.lam), dev(ft_wl.w), c["K_pre"], c["alpha_pre"],
+                                    c["K_ft"], c["alpha_ft"])
+    assert rel_l2(host(got), c["chain3"]) < 1e-4

@@ -710,3 +710,27 @@ def test_chain3_truncated_series_against_dense_autograd_matrices(act, skip):
     got = orc.hypergrad_chain3(pre, ft, w, theta, v, K1, a1, K2, a2)
     assert rel_l2(got, expect) < 1e-10
     assert rel_l2(orc.best_response_neumann(ft, v, w, gv, K2, a2), u) < 1e-11
+
+
+# ---------------------------------------------------------------- stored expectations
+
+def test_oracle_reproduces_the_stored_tiny_hypergradients():
+    """tests/golden/tiny_hypergradients.json is written by tests/golden/make_golden.py from the
+    oracle; the oracle of today must still produce it (a deliberate change regenerates the file)."""
+    import json
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "tiny_hypergradients.json")
+    gold = json.load(open(path))
+    for case in gold["cases"]:
+        cfg = {k: (tuple(v) if isinstance(v, list) else v) for k, v in case["cfg"].items()}
+        wl = wk.tiny(**cfg)
+        prob = oracle_problem(wl)
+        w, lam = wl.w.astype(np.float64), wl.lam.astype(np.float64)
+        assert rel_l2(orc.hypergrad_neumann(prob, w, lam, case["K"], case["alpha"]), case["neumann"]) < 1e-12
+        assert rel_l2(orc.hypergrad_fd(prob, w, lam, case["K"], case["alpha"], case["eps_scale"]), case["fd"]) < 1e-9
+        assert rel_l2(orc.hypergrad_cg(prob, w, lam, 3), case["cg"]) < 1e-10
+    c = gold["chain3"]
+    pre_wl, ft_wl = wk.chain3(seed=c["seed"], act="gelu", skip_last=True)
+    got = orc.hypergrad_chain3(oracle_problem(pre_wl), oracle_problem(ft_wl), pre_wl.w, pre_wl.lam, ft_wl.w,
+                               c["K_pre"], c["alpha_pre"], c["K_ft"], c["alpha_ft"])
+    assert rel_l2(got, c["chain3"]) < 1e-12
