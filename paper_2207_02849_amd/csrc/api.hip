@@ -489,10 +489,10 @@ void wgrad_batch(betty_handle h, OperandSet& os, int side, bool rop, const Wgrad
 // `vflat` (for the bias directions).  Leaves Rz_l (fp32) and Ra_l.
 // With fuse_hessian (outputs of at most 32 columns) the last layer's epilogue applies the loss
 // Hessian and leaves R delta_L instead of Rz_L.
-void r_forward(betty_handle h, OperandSet& os, const float* vflat, bool fuse_hessian = false) {
+void r_forward(betty_handle h, OperandSet& os, const float* vflat, bool fuse_hessian = false, int upto = 0) {
   SideBuf& sb = os.side[0];
   const int L = h->L, B = sb.B, Bp = sb.Bp;
-  for (int l = 1; l <= L; ++l) {
+  for (int l = 1; l <= (upto > 0 ? upto : L); ++l) {
     const LayerInfo& li = h->layers[l - 1];
     const bool last = l == L;
     const void* a_prev = l == 1 ? h->at<void>(sb.X) : h->at<void>(sb.A[l - 1]);
@@ -540,13 +540,33 @@ void hvp_cached(betty_handle h, OperandSet& os, const float* vflat, const WgradS
   const int L = h->L, B = sb.B, Bp = sb.Bp;
   const bool pipe = pipelined && h->side_stream && L >= 2;
   const LayerInfo& lo = h->layers[L - 1];
-  const bool fused_hessian = lo.n_out <= 32;
-  r_forward(h, os, vflat, fused_hessian);
-  if (!fused_hessian)
-    launch_loss_hessian_rows(h->ctx, os.elem, h->desc.loss, h->f(sb.P), h->f(os.Rz[L]), lo.n_out_p, h->f(sb.s), B,
-                             lo.n_out, h->at<void>(os.RD[L]), lo.n_out_p, h->at<void>(os.RDt[L]), Bp);
-  if (pipe) side_wgrad(h, os, sink, L);
-  for (int l = L; l >= 2; --l) {
+  // a narrow output layer goes through one vector kernel: last R-forward product, loss Hessian and
+  // the R-backward step through that layer
+  const bool narrow_last = L >= 2 && lo.n_out <= LAST_ROP_MAX_C;
+  const bool fused_hessian = !narrow_last && lo.n_out <= 32;
+  r_forward(h, os, vflat, fused_hessian, narrow_last ? L - 1 : 0);
+  if (narrow_last) {
+    LastRopArgs a{};
+    a.RA = h->at<void>(os.RA[L - 1]); a.A = h->at<void>(sb.A[L - 1]); a.lda = lo.n_in_p;
+    a.Wt = h->at<void>(os.Wt[L - 1]); a.Vt = h->at<void>(os.Vt[L - 1]); a.ldt = lo.n_in_p;
+    a.Wn = h->at<void>(os.Wn[L - 1]); a.Vn = h->at<void>(os.Vn[L - 1]); a.ldn = lo.n_out_p;
+    a.cbias = h->desc.has_bias ? vflat + lo.b_off : nullptr;
+    a.P = h->f(sb.P); a.s = h->f(sb.s); a.ldp = lo.n_out_p;
+    a.DL = h->at<void>(sb.D[L]); a.ldd = lo.n_out_p;
+    a.dphi = h->f(sb.dphi[L - 1]); a.e2 = sb.e2[L - 1] ? h->f(sb.e2[L - 1]) : nullptr;
+    a.Rz = h->f(os.Rz[L - 1]); a.ldf = lo.n_in_p;
+    a.RDL = h->at<void>(os.RD[L]); a.RDLt = h->at<void>(os.RDt[L]); a.ldRDLt = Bp;
+    a.RD = h->at<void>(os.RD[L - 1]); a.ldRD = lo.n_in_p; a.RDt = h->at<void>(os.RDt[L - 1]); a.ldRDt = Bp;
+    a.B = B; a.n_in = lo.n_in; a.n_in_p = lo.n_in_p; a.C = lo.n_out; a.loss = h->desc.loss;
+    launch_last_layer_rop(h->ctx, os.elem, a);
+    if (pipe) { side_wgrad(h, os, sink, L); side_wgrad(h, os, sink, L - 1); }
+  } else {
+    if (!fused_hessian)
+      launch_loss_hessian_rows(h->ctx, os.elem, h->desc.loss, h->f(sb.P), h->f(os.Rz[L]), lo.n_out_p, h->f(sb.s), B,
+                               lo.n_out, h->at<void>(os.RD[L]), lo.n_out_p, h->at<void>(os.RDt[L]), Bp);
+    if (pipe) side_wgrad(h, os, sink, L);
+  }
+  for (int l = narrow_last ? L - 1 : L; l >= 2; --l) {
     const LayerInfo& li = h->layers[l - 1];
     Epilogue e = blank_epilogue(EPI_RBWD);
     e.dphi = h->f(sb.dphi[l - 1]);

@@ -31,28 +31,6 @@
 
 namespace betty {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte chunk
-
-template <typename T> struct MfmaChunk;
-
-template <> struct MfmaChunk<__bf16> {
-  static __device__ __forceinline__ void run(const u32x4& a, const u32x4& b, f32x16& acc) {
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
-                                                  acc, 0, 0, 0);
-  }
-};
-
-template <> struct MfmaChunk<float> {
-  static __device__ __forceinline__ void run(const u32x4& a, const u32x4& b, f32x16& acc) {
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
-  }
-};
-
 // ------------------------------------------------------------------------------------------
 // epilogue helpers
 // ------------------------------------------------------------------------------------------

@@ -111,6 +111,32 @@ struct Launch {   // RAII bracket around one kernel launch
   ~Launch() { c.end(); }
 };
 
+// One 16-byte chunk of K for a 32 x 32 MFMA block: 8 bf16 (one v_mfma_f32_32x32x16_bf16) or 4 floats
+// (four v_mfma_f32_32x32x2_f32).  Lane l supplies row l % 32 of A and of B; lanes 0-31 hold the
+// even chunks of a chunk pair, lanes 32-63 the odd ones.  Register r of lane l of the result holds
+// C[8*(r/4) + 4*(l/32) + r%4][l%32].
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte chunk
+
+template <typename T> struct MfmaChunk;
+
+template <> struct MfmaChunk<__bf16> {
+  static __device__ __forceinline__ void run(const u32x4& a, const u32x4& b, f32x16& acc) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
+                                                  acc, 0, 0, 0);
+  }
+};
+
+template <> struct MfmaChunk<float> {
+  static __device__ __forceinline__ void run(const u32x4& a, const u32x4& b, f32x16& acc) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+  }
+};
+
 // ---- gemm.hip
 int gemm_ktile_elems(Elem elem);
 int gemm_cfg_tile(int cfg);
@@ -147,6 +173,26 @@ struct LossArgs {
 struct LossBatch { int n = 0; LossArgs a[2]; };     // up to two batches (train, validation) per launch
 void launch_loss_rows(Ctx&, Elem, const LossBatch&);
 // Rdelta_L (fp32) = s_i * (d^2 l_i/dz^2) Rz_i
+// The last layer of the R-op passes when the network output is narrow (at most 16 columns): one
+// launch computes Rz_L = Ra_{L-1} W_L + a_{L-1} V_L + c_L, applies the loss Hessian (R delta_L) and
+// propagates through the last layer, R delta_{L-1} = (R delta_L W_L^T + delta_L V_L^T) .* phi'
+// + e2 .* Rz_{L-1}, with plain vector arithmetic (the products have 16 or fewer columns or
+// reduction terms, a poor fit for 32-wide MFMA tiles).
+struct LastRopArgs {
+  const void* RA; const void* A; int lda;               // Ra_{L-1}, a_{L-1}: [B][n_in_p], operand type
+  const void* Wt; const void* Vt; int ldt;              // W_L, V_L as [n_out_p][n_in_p]
+  const void* Wn; const void* Vn; int ldn;              // W_L, V_L as [n_in_p][n_out_p]
+  const float* cbias;                                   // bias direction of the last layer, or null
+  const float* P; const float* s; int ldp;              // softmax probabilities [B][ldp], per-sample scale
+  const void* DL; int ldd;                              // delta_L [B][ldd], operand type
+  const float* dphi; const float* e2; const float* Rz; int ldf;   // layer L-1, fp32 [B][ldf]; e2 may be null
+  void* RDL; void* RDLt; int ldRDLt;                    // out: R delta_L [B][ldd] and [n_out_p][ldRDLt]
+  void* RD; int ldRD; void* RDt; int ldRDt;             // out: R delta_{L-1} [B][ldRD] and [n_in_p][ldRDt]
+  int B, n_in, n_in_p, C, loss;
+};
+constexpr int LAST_ROP_MAX_C = 16;
+void launch_last_layer_rop(Ctx&, Elem, const LastRopArgs&);
+
 void launch_loss_hessian_rows(Ctx&, Elem, int loss, const float* P, const float* Rz, long long ld,
                               const float* s, int rows, int C, void* D, int ldD, void* Dt, int ldDt);
 // c_i = < dl_i/dz, Rz_i >

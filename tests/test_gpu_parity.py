@@ -132,6 +132,9 @@ def test_tiny_bf16(cfg):
     dict(kind="reweight", act="gelu", loss="ce", dims=(257, 129, 33), batch=200, hidden=100),
     dict(kind="l2", act="relu", loss="ce", dims=(130, 260, 7), batch=70),
     dict(kind="proximal", act="gelu", loss="ce", dims=(200, 140, 130, 9), batch=150, prox_rho=0.02, prox_skip_last=True),
+    # 24 outputs: too wide for the narrow-output vector kernel, narrow enough for the loss Hessian in the GEMM epilogue
+    dict(kind="reweight", act="gelu", loss="ce", dims=(70, 50, 24), batch=37, hidden=9),
+    dict(kind="l2", act="gelu", loss="mse", dims=(70, 50, 16), batch=37),
 ])
 @pytest.mark.parametrize("prec", ["fp32", "bf16"])
 def test_ragged_multi_tile(cfg, prec):
