@@ -70,23 +70,27 @@ template <> __device__ __forceinline__ void store4<__bf16>(__bf16* p, const floa
 // (before the loop) issues every load the mode needs for the block's 16 elements into EpiRegs;
 // epi_finish (after the loop) computes and stores.  Nothing the prefetch reads is written by the
 // same launch before epi_finish of the same element.
-struct EpiRegs { float a[16], b[16], c[16], d[16]; float colv; };
+// NR = 16: a whole block;  NR = 4: one register quad (four consecutive rows), rb already at its first row.
+template <int NR> struct EpiRegs { float a[NR], b[NR], c[NR], d[NR]; float colv; };
 
+template <int NR> __device__ __forceinline__ int epi_row(int rb, int k) { return NR == 16 ? rb + 8 * (k >> 2) + (k & 3) : rb + k; }
+
+template <int NR>
 __device__ __forceinline__ int epi_offset(int rb, int k, long long ld, int col) {
-  return (int)((long long)(rb + 8 * (k >> 2) + (k & 3)) * ld + col);   // layer slices are < 2^31 elements
+  return (int)((long long)epi_row<NR>(rb, k) * ld + col);   // layer slices are < 2^31 elements
 }
 
-template <int MODE>
-__device__ __forceinline__ void epi_prefetch(const Epilogue& e, int M, int N, int rb, int col, EpiRegs& R) {
+template <int MODE, int NR>
+__device__ __forceinline__ void epi_prefetch(const Epilogue& e, int M, int N, int rb, int col, EpiRegs<NR>& R) {
   if constexpr (MODE == EPI_RFWD_LAST_HESS) {
     // every lane of the block takes part in the row sums later: lanes outside the valid extent hold zeros
     const bool colok = col < N;
     R.colv = (colok && e.colvec) ? e.colvec[col] : 0.f;
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
-      const int row = rb + 8 * (k >> 2) + (k & 3);
+    for (int k = 0; k < NR; ++k) {
+      const int row = epi_row<NR>(rb, k);
       const bool ok = colok && row < M;
-      R.a[k] = (ok && e.dphi) ? e.dphi[epi_offset(rb, k, e.ldf, col)] : 0.f;
+      R.a[k] = (ok && e.dphi) ? e.dphi[epi_offset<NR>(rb, k, e.ldf, col)] : 0.f;
       R.b[k] = ok ? e.e[row] : 0.f;
     }
     return;
@@ -96,9 +100,9 @@ __device__ __forceinline__ void epi_prefetch(const Epilogue& e, int M, int N, in
   if constexpr (MODE == EPI_FWD || MODE == EPI_FWD_LAST || MODE == EPI_RFWD || MODE == EPI_RFWD_LAST)
     R.colv = e.colvec ? e.colvec[col] : 0.f;
 #pragma unroll
-  for (int k = 0; k < 16; ++k) {
-    const bool ok = rb + 8 * (k >> 2) + (k & 3) < M;
-    const int o = epi_offset(rb, k, ldx, col);
+  for (int k = 0; k < NR; ++k) {
+    const bool ok = epi_row<NR>(rb, k) < M;
+    const int o = epi_offset<NR>(rb, k, ldx, col);
     if constexpr (MODE == EPI_BWD) {
       R.a[k] = ok ? e.dphi[o] : 0.f;
       R.b[k] = (ok && e.e_io) ? e.e_io[o] : 0.f;
@@ -129,16 +133,16 @@ __device__ __forceinline__ void epi_prefetch(const Epilogue& e, int M, int N, in
   }
 }
 
-template <typename T, int MODE>
+template <typename T, int MODE, int NR>
 __device__ __forceinline__ void epi_finish(const Epilogue& e, int M, int N, int rb, int col,
-                                           const f32x16 acc, const EpiRegs& R) {
-  float val[16];
+                                           const float (&acc)[NR], const EpiRegs<NR>& R) {
+  float val[NR];
   if constexpr (MODE == EPI_RFWD_LAST_HESS) {
     // rows live across the 32 lanes of a half-wavefront (lane % 32 = column): butterfly sums
     const bool colok = col < N;
-    float rz[16], dot[16];
+    float rz[NR], dot[NR];
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
+    for (int k = 0; k < NR; ++k) {
       rz[k] = colok ? acc[k] + R.colv : 0.f;
       dot[k] = R.a[k] * rz[k];
     }
@@ -146,89 +150,89 @@ __device__ __forceinline__ void epi_finish(const Epilogue& e, int M, int N, int 
 #pragma unroll
       for (int o = 16; o > 0; o >>= 1)
 #pragma unroll
-        for (int k = 0; k < 16; ++k) dot[k] += __shfl_xor(dot[k], o, 64);
+        for (int k = 0; k < NR; ++k) dot[k] += __shfl_xor(dot[k], o, 64);
 #pragma unroll
-      for (int k = 0; k < 16; ++k) val[k] = R.b[k] * (R.a[k] * rz[k] - R.a[k] * dot[k]);
+      for (int k = 0; k < NR; ++k) val[k] = R.b[k] * (R.a[k] * rz[k] - R.a[k] * dot[k]);
     } else {
 #pragma unroll
-      for (int k = 0; k < 16; ++k) val[k] = R.b[k] * 2.f * rz[k];
+      for (int k = 0; k < NR; ++k) val[k] = R.b[k] * 2.f * rz[k];
     }
   }
   if (col >= N || rb >= M) return;
   const long long ldx = MODE >= EPI_WGRAD ? e.ldc : e.ldf;
-  bool ok[16];
-  int of[16];
+  bool ok[NR];
+  int of[NR];
 #pragma unroll
-  for (int k = 0; k < 16; ++k) {
-    ok[k] = rb + 8 * (k >> 2) + (k & 3) < M;
-    of[k] = epi_offset(rb, k, ldx, col);
+  for (int k = 0; k < NR; ++k) {
+    ok[k] = epi_row<NR>(rb, k) < M;
+    of[k] = epi_offset<NR>(rb, k, ldx, col);
   }
   if constexpr (MODE == EPI_RFWD_LAST_HESS) {
     // val is set; fall through to the operand copies
   } else if constexpr (MODE == EPI_FWD) {
-    float d1[16], d2[16];
+    float d1[NR], d2[NR];
 #pragma unroll
-    for (int k = 0; k < 16; ++k) act_eval(e.act, acc[k] + R.colv, val[k], d1[k], d2[k]);
+    for (int k = 0; k < NR; ++k) act_eval(e.act, acc[k] + R.colv, val[k], d1[k], d2[k]);
 #pragma unroll
-    for (int k = 0; k < 16; ++k)
+    for (int k = 0; k < NR; ++k)
       if (ok[k]) e.dphi_out[of[k]] = d1[k];
     if (e.d2_out) {
 #pragma unroll
-      for (int k = 0; k < 16; ++k)
+      for (int k = 0; k < NR; ++k)
         if (ok[k]) e.d2_out[of[k]] = d2[k];
     }
   } else if constexpr (MODE == EPI_FWD_LAST || MODE == EPI_RFWD_LAST) {
 #pragma unroll
-    for (int k = 0; k < 16; ++k)
+    for (int k = 0; k < NR; ++k)
       if (ok[k]) e.f0[of[k]] = acc[k] + R.colv;
     return;
   } else if constexpr (MODE == EPI_BWD) {
     if (e.e_io) {
 #pragma unroll
-      for (int k = 0; k < 16; ++k)
+      for (int k = 0; k < NR; ++k)
         if (ok[k]) e.e_io[of[k]] = acc[k] * R.b[k];
     }
 #pragma unroll
-    for (int k = 0; k < 16; ++k) val[k] = acc[k] * R.a[k];
+    for (int k = 0; k < NR; ++k) val[k] = acc[k] * R.a[k];
   } else if constexpr (MODE == EPI_RFWD) {
 #pragma unroll
-    for (int k = 0; k < 16; ++k)
+    for (int k = 0; k < NR; ++k)
       if (ok[k]) e.f0[of[k]] = acc[k] + R.colv;
 #pragma unroll
-    for (int k = 0; k < 16; ++k) val[k] = R.a[k] * (acc[k] + R.colv);
+    for (int k = 0; k < NR; ++k) val[k] = R.a[k] * (acc[k] + R.colv);
   } else if constexpr (MODE == EPI_RBWD) {
 #pragma unroll
-    for (int k = 0; k < 16; ++k) val[k] = acc[k] * R.a[k] + R.b[k] * R.c[k];
+    for (int k = 0; k < NR; ++k) val[k] = acc[k] * R.a[k] + R.b[k] * R.c[k];
   } else if constexpr (MODE == EPI_WGRAD) {            // C = acc (+ 2 e^lam x)
     if (e.lam) {
 #pragma unroll
-      for (int k = 0; k < 16; ++k)
+      for (int k = 0; k < NR; ++k)
         if (ok[k]) e.C[of[k]] = acc[k] + 2.f * expf(R.a[k]) * R.b[k];
     } else {
 #pragma unroll
-      for (int k = 0; k < 16; ++k)
+      for (int k = 0; k < NR; ++k)
         if (ok[k]) e.C[of[k]] = acc[k];
     }
     return;
   } else if constexpr (MODE == EPI_WGRAD_INIT) {       // v = acc (and p = acc if asked); operand copies
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
+    for (int k = 0; k < NR; ++k) {
       val[k] = acc[k];
       if (ok[k]) { e.v[of[k]] = acc[k]; if (e.p) e.p[of[k]] = acc[k]; }
     }
   } else if constexpr (MODE == EPI_WGRAD_NEUMANN) {    // Hs = acc (+ 2 e^lam s); s <- g + s - alpha Hs
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
+    for (int k = 0; k < NR; ++k) {
       float hs = acc[k];
       if (e.lam) hs += 2.f * expf(R.c[k]) * R.a[k];
       val[k] = R.b[k] + (R.a[k] - e.alpha * hs);
     }
 #pragma unroll
-    for (int k = 0; k < 16; ++k)
+    for (int k = 0; k < NR; ++k)
       if (ok[k]) e.p[of[k]] = val[k];
   } else if constexpr (MODE == EPI_WGRAD_SGD) {          // lower optimiser step: momentum SGD in place
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
+    for (int k = 0; k < NR; ++k) {
       float gk = acc[k] + e.gamma * R.b[k];
       if (e.lam) gk += 2.f * expf(R.c[k]) * (R.b[k] - R.d[k]);     // x: anchor of a proximal term
       const float mk = e.beta * R.a[k] + gk;
@@ -237,7 +241,7 @@ __device__ __forceinline__ void epi_finish(const Epilogue& e, int M, int N, int 
     return;
   } else if constexpr (MODE == EPI_WGRAD_NEUMANN_L2) {  // final step: only d(lambda) leaves the kernel
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
+    for (int k = 0; k < NR; ++k) {
       const float el = 2.f * expf(R.c[k]);
       const float sn = R.b[k] + (R.a[k] - e.alpha * (acc[k] + el * R.a[k]));
       if (ok[k]) e.C[of[k]] = -el * R.d[k] * (e.alpha * sn);
@@ -249,18 +253,18 @@ __device__ __forceinline__ void epi_finish(const Epilogue& e, int M, int N, int 
   // operand-typed copies: row-major element by element, transposed as 4-element vectors; rows
   // beyond M are written as zeros (they are padding of the transposed operand)
 #pragma unroll
-  for (int k = 0; k < 16; ++k)
+  for (int k = 0; k < NR; ++k)
     if (!ok[k]) val[k] = 0.f;
   if (e.out) {
     T* o = (T*)e.out;
 #pragma unroll
-    for (int k = 0; k < 16; ++k)
-      if (ok[k]) store1<T>(o + (long long)(rb + 8 * (k >> 2) + (k & 3)) * e.ld + col, val[k]);
+    for (int k = 0; k < NR; ++k)
+      if (ok[k]) store1<T>(o + (long long)epi_row<NR>(rb, k) * e.ld + col, val[k]);
   }
   if (e.outT) {
     T* o = (T*)e.outT + (long long)col * e.ldT + rb;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int q = 0; q < NR / 4; ++q) {
       const float quad[4] = {val[4 * q], val[4 * q + 1], val[4 * q + 2], val[4 * q + 3]};
       if (rb + 8 * q < M) store4<T>(o + 8 * q, quad);
     }
@@ -384,14 +388,21 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
   // group 0 finishes the tile.  (With several blocks per wavefront the prefetch is kept for the
   // parameter-shaped modes, whose epilogue moves far more bytes than their k loop.)
   constexpr bool PREFETCH = TM * TN == 1 || (MODE >= EPI_WGRAD && BM == 64);
+  // One-wavefront K groups: the tile is a single MFMA block, and once the groups' partial sums are
+  // in LDS the first four wavefronts each finish one register quad of it (four consecutive rows
+  // per lane), so the epilogue's arithmetic and stores run on four wavefronts instead of one.
+  constexpr bool SPLIT_EPI = WPG == 1 && KG >= 4;
   const Epilogue& e = batch.p[pi].e;
-  EpiRegs pre[TM * TN];
-  if constexpr (PREFETCH) {
+  EpiRegs<16> pre[SPLIT_EPI ? 1 : TM * TN];
+  EpiRegs<4> pre4;
+  if constexpr (SPLIT_EPI) {
+    if (kg < 4) epi_prefetch<MODE, 4>(e, g.M, g.N, m0 + 8 * kg + 4 * (lane >> 5), n0 + (lane & 31), pre4);
+  } else if constexpr (PREFETCH) {
     if (kg == 0) {
 #pragma unroll
       for (int ij = 0; ij < TM * TN; ++ij)
-        epi_prefetch<MODE>(e, g.M, g.N, m0 + wm * TM * 32 + (ij / TN) * 32 + 4 * (lane >> 5),
-                           n0 + wn * TN * 32 + (ij % TN) * 32 + (lane & 31), pre[ij]);
+        epi_prefetch<MODE, 16>(e, g.M, g.N, m0 + wm * TM * 32 + (ij / TN) * 32 + 4 * (lane >> 5),
+                               n0 + wn * TN * 32 + (ij % TN) * 32 + (lane & 31), pre[ij]);
     }
   }
 
@@ -480,7 +491,24 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
 #undef BETTY_GROUP_SYNC
 
   // ---- combine the K groups through LDS in group order (bit-reproducible); group 0 finishes
-  if constexpr (KG > 1) {
+  if constexpr (SPLIT_EPI) {
+    __syncthreads();                                // all groups are done with the operand tiles
+    float* red = (float*)smem;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[(kg * 16 + r) * 64 + lane] = acc[0][r];
+    __syncthreads();
+    if (kg >= 4) return;
+    float q4[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) q4[r] = red[(4 * kg + r) * 64 + lane];
+#pragma unroll 1
+    for (int g2 = 1; g2 < KG; ++g2) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) q4[r] += red[((g2 * 16) + 4 * kg + r) * 64 + lane];
+    }
+    epi_finish<T, MODE, 4>(e, g.M, g.N, m0 + 8 * kg + 4 * (lane >> 5), n0 + (lane & 31), q4, pre4);
+    return;
+  } else if constexpr (KG > 1) {
     __syncthreads();                                // all groups are done with the operand tiles
     float* red = (float*)smem;
     if (kg > 0) {
@@ -505,8 +533,11 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
   for (int ij = 0; ij < TM * TN; ++ij) {
     const int rb = m0 + wm * TM * 32 + (ij / TN) * 32 + 4 * (lane >> 5);
     const int col = n0 + wn * TN * 32 + (ij % TN) * 32 + (lane & 31);
-    if constexpr (!PREFETCH) epi_prefetch<MODE>(e, g.M, g.N, rb, col, pre[ij]);
-    epi_finish<T, MODE>(e, g.M, g.N, rb, col, acc[ij], pre[ij]);
+    if constexpr (!PREFETCH) epi_prefetch<MODE, 16>(e, g.M, g.N, rb, col, pre[ij]);
+    float accf[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) accf[r] = acc[ij][r];
+    epi_finish<T, MODE, 16>(e, g.M, g.N, rb, col, accf, pre[ij]);
   }
 }
 
@@ -517,7 +548,7 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
 template <typename T, int BT, int WPG, int KG>
 constexpr size_t lds_bytes() {
   constexpr size_t operands = (size_t)(KG == 1 ? 2 : KG) * 2 * BT * (GEMM_NCH + 1) * 16;
-  constexpr size_t reduce = (size_t)(KG - 1) * BT * BT * 4;
+  constexpr size_t reduce = (size_t)(WPG == 1 ? KG : KG - 1) * BT * BT * 4;
   return operands > reduce ? operands : reduce;
 }
 
