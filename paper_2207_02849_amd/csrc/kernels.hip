@@ -242,61 +242,103 @@ __global__ __launch_bounds__(256) void loss_directional_rows_kernel(int loss, co
 // last layer of the R-op passes for narrow outputs (see LastRopArgs)
 // ------------------------------------------------------------------------------------------
 
-// Workgroup = 8 wavefronts (256 registers per lane: phase 3 keeps 2 x 64 LDS values live),
-// 4 samples.  Phase 1: lane (s, c) of wavefront ks sums its k-slice of Ra W + a V in 16-byte
-// chunks (both operands K-major); the 8 slices are combined through LDS in slice order.  Phase 2 (one wavefront): loss Hessian per sample, 16-lane butterflies.  Phase 3:
-// thread j propagates the four samples through row j of W_L, V_L.
+// Workgroup = 16 wavefronts, 4 samples.  Both small products run as zero-padded 32 x 32 MFMA
+// blocks (rows = the 4 samples; only lanes that own a real operand row load anything):
+//  phase 1  Rz_L block (4 x C): K = n_in sliced over the wavefronts in chunk pairs, partial blocks
+//           combined through LDS in wavefront order;
+//  phase 2  (one wavefront) loss Hessian per sample with 16-lane butterflies -> R delta_L, kept in
+//           LDS in operand type next to delta_L;
+//  phase 3  each wavefront takes 32 columns j at a time: (R delta_L W^T + delta_L V^T) is one
+//           chunk pair of K = 16 classes, then the elementwise part and both output copies.
 template <typename T>
-__global__ __launch_bounds__(512) void last_layer_rop_kernel(LastRopArgs a) {
-  constexpr int S = 4, CP = LAST_ROP_MAX_C, EPC = 16 / (int)sizeof(T), NW = 8;
-  typedef __attribute__((__vector_size__(EPC * sizeof(T)))) T chunk_t;
+__global__ __launch_bounds__(1024) void last_layer_rop_kernel(LastRopArgs a) {
+  constexpr int S = 4, CP = LAST_ROP_MAX_C, EPC = 16 / (int)sizeof(T), NW = 16, U = sizeof(T) == 4 ? 2 : 4;
   __shared__ float part[NW][S * CP];
-  __shared__ float rd[S][CP], dl[S][CP];
+  __shared__ __attribute__((aligned(16))) T rdT[32][CP], dlT[32][CP];   // rows >= S stay zero
   const int t = threadIdx.x, lane = t & 63, ks = t >> 6;
-  const int s = lane >> 4, c = lane & 15;
+  const int row = lane & 31, half = lane >> 5;
   // blockIdx.y splits the columns j of phase 3; every split repeats phases 1-2 for its samples
   // (cheap), the first one writes R delta_L
-  const int i0 = blockIdx.x * S, i = i0 + s;
-  const int jsplit = (a.n_in + gridDim.y - 1) / gridDim.y;
+  const int i0 = blockIdx.x * S;
+  const int jsplit = ((a.n_in + gridDim.y - 1) / gridDim.y + 31) / 32 * 32;
   const int j_begin = blockIdx.y * jsplit, j_end = min(a.n_in, j_begin + jsplit);
-  const T* RA = (const T*)a.RA;
-  const T* A = (const T*)a.A;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  for (int x = t; x < 32 * CP; x += 64 * NW) { (&rdT[0][0])[x] = from_float<T>(0.f); (&dlT[0][0])[x] = from_float<T>(0.f); }
 
-  // ---- phase 1: the 4 x C block of Rz_L as one zero-padded 32 x 32 MFMA block per wavefront
-  // (rows = samples, columns = classes), K sliced over the wavefronts; only the lanes that own a
-  // real row of an operand load anything
+  // Everything phases 2 and 3 read from memory is independent of phase 1: request it now, so the
+  // kernel pays one memory round trip instead of three.  (The launcher sizes the column splits so
+  // that a wavefront has at most one block of 32 columns.)
+  const int jb = j_begin + ks * 32;
+  const bool jb_ok = jb < j_end;
+  const int j = jb + lane;
+  const bool j_ok = jb_ok && lane < 32 && j < j_end;
+  u32x4 w3[CP / (2 * EPC)], v3[CP / (2 * EPC)];
+  float dphi3[S], e23[S], rz3[S];
+#pragma unroll
+  for (int p = 0; p < CP / (2 * EPC); ++p) { w3[p] = zero; v3[p] = zero; }
+#pragma unroll
+  for (int ss = 0; ss < S; ++ss) { dphi3[ss] = 0.f; e23[ss] = 0.f; rz3[ss] = 0.f; }
+  if (jb_ok) {
+    const int jr = jb + row;                                // < n_in_p: rows beyond n_in are zero padding
+    const T* wr = (const T*)a.Wn + (long long)jr * a.ldn + half * EPC;
+    const T* vr = (const T*)a.Vn + (long long)jr * a.ldn + half * EPC;
+#pragma unroll
+    for (int p = 0; p < CP / (2 * EPC); ++p) {
+      w3[p] = *(const u32x4*)(wr + p * 2 * EPC);
+      v3[p] = *(const u32x4*)(vr + p * 2 * EPC);
+    }
+  }
+  if (j_ok) {
+#pragma unroll
+    for (int ss = 0; ss < S; ++ss)
+      if (i0 + ss < a.B) {
+        const long long f = (long long)(i0 + ss) * a.ldf + j;
+        dphi3[ss] = a.dphi[f];
+        if (a.e2) { e23[ss] = a.e2[f]; rz3[ss] = a.Rz[f]; }
+      }
+  }
+  float p2 = 0.f, s2 = 0.f, cb2 = 0.f;
+  T d2 = from_float<T>(0.f);
+  if (ks == 0) {
+    const int s = lane >> 4, c = lane & 15, i = i0 + s;
+    if (c < a.C && i < a.B) {
+      if (a.loss == BETTY_LOSS_SOFTMAX_CE) p2 = a.P[(long long)i * a.ldp + c];
+      s2 = a.s[i];
+      if (a.cbias) cb2 = a.cbias[c];
+      d2 = ((const T*)a.DL)[(long long)i * a.ldd + c];
+    }
+  }
+
+  // ---- phase 1
   {
     f32x16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    const int row = lane & 31, half = lane >> 5;
     const bool a_ok = row < S && i0 + row < a.B, b_ok = row < a.C;
-    const int kslice = a.n_in_p / NW;                       // multiple of 16 elements (n_in_p % 128 == 0)
-    const long long koff = (long long)ks * kslice + half * EPC;
-    const T* ra = RA + (long long)(i0 + row) * a.lda + koff;
-    const T* av = A + (long long)(i0 + row) * a.lda + koff;
-    const T* w = (const T*)a.Wt + (long long)row * a.ldt + koff;
-    const T* v = (const T*)a.Vt + (long long)row * a.ldt + koff;
-    const u32x4 zero = {0u, 0u, 0u, 0u};
-    constexpr int U = 4;                                    // chunk pairs whose loads are issued together
-    for (int k0 = 0; k0 < kslice; k0 += U * 2 * EPC) {
+    const int pairs = a.n_in_p / (2 * EPC), per = (pairs + NW - 1) / NW;
+    const int p_begin = ks * per, p_end = min(pairs, p_begin + per);
+    const T* ra = (const T*)a.RA + (long long)(i0 + row) * a.lda + half * EPC;
+    const T* av = (const T*)a.A + (long long)(i0 + row) * a.lda + half * EPC;
+    const T* w = (const T*)a.Wt + (long long)row * a.ldt + half * EPC;
+    const T* v = (const T*)a.Vt + (long long)row * a.ldt + half * EPC;
+    for (int p0 = p_begin; p0 < p_end; p0 += U) {
       u32x4 r8[U], a8[U], w8[U], v8[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) { r8[u] = zero; a8[u] = zero; w8[u] = zero; v8[u] = zero; }
       if (a_ok) {
 #pragma unroll
         for (int u = 0; u < U; ++u)
-          if (k0 + u * 2 * EPC < kslice) {
-            r8[u] = *(const u32x4*)(ra + k0 + u * 2 * EPC);
-            a8[u] = *(const u32x4*)(av + k0 + u * 2 * EPC);
+          if (p0 + u < p_end) {
+            r8[u] = *(const u32x4*)(ra + (p0 + u) * 2 * EPC);
+            a8[u] = *(const u32x4*)(av + (p0 + u) * 2 * EPC);
           }
       }
       if (b_ok) {
 #pragma unroll
         for (int u = 0; u < U; ++u)
-          if (k0 + u * 2 * EPC < kslice) {
-            w8[u] = *(const u32x4*)(w + k0 + u * 2 * EPC);
-            v8[u] = *(const u32x4*)(v + k0 + u * 2 * EPC);
+          if (p0 + u < p_end) {
+            w8[u] = *(const u32x4*)(w + (p0 + u) * 2 * EPC);
+            v8[u] = *(const u32x4*)(v + (p0 + u) * 2 * EPC);
           }
       }
 #pragma unroll
@@ -315,16 +357,16 @@ __global__ __launch_bounds__(512) void last_layer_rop_kernel(LastRopArgs a) {
 
   // ---- phase 2
   if (ks == 0) {
+    const int s = lane >> 4, c = lane & 15, i = i0 + s;
     float rz = 0.f;
 #pragma unroll
     for (int q = 0; q < NW; ++q) rz += part[q][lane];
     const bool ok = c < a.C && i < a.B;
-    if (ok && a.cbias) rz += a.cbias[c];
-    if (!ok) rz = 0.f;
-    const float si = ok ? a.s[i] : 0.f;
+    rz = ok ? rz + cb2 : 0.f;
+    const float si = s2;
     float val;
     if (a.loss == BETTY_LOSS_SOFTMAX_CE) {
-      const float p = ok ? a.P[(long long)i * a.ldp + c] : 0.f;
+      const float p = p2;
       float dot = p * rz;
 #pragma unroll
       for (int o = 8; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
@@ -333,46 +375,46 @@ __global__ __launch_bounds__(512) void last_layer_rop_kernel(LastRopArgs a) {
       val = si * 2.f * rz;
     }
     const T vt = from_float<T>(val);
-    rd[s][c] = ok ? to_float<T>(vt) : 0.f;
-    dl[s][c] = ok ? to_float<T>(((const T*)a.DL)[(long long)i * a.ldd + c]) : 0.f;
-    if (ok && blockIdx.y == 0) {
-      ((T*)a.RDL)[(long long)i * a.ldd + c] = vt;
-      ((T*)a.RDLt)[(long long)c * a.ldRDLt + i] = vt;
+    if (ok) {
+      rdT[s][c] = vt;
+      dlT[s][c] = d2;
+      if (blockIdx.y == 0) {
+        ((T*)a.RDL)[(long long)i * a.ldd + c] = vt;
+        ((T*)a.RDLt)[(long long)c * a.ldRDLt + i] = vt;
+      }
     }
   }
   __syncthreads();
 
   // ---- phase 3
-#pragma unroll 1
-  for (int j = j_begin + t; j < j_end; j += 64 * NW) {
-    const T* wr = (const T*)a.Wn + (long long)j * a.ldn;
-    const T* vr = (const T*)a.Vn + (long long)j * a.ldn;
-    float w[CP], v[CP];
+  if (jb_ok) {
+    f32x16 acc;
 #pragma unroll
-    for (int q = 0; q < CP / EPC; ++q) {
-      const chunk_t w8 = *(const chunk_t*)(wr + q * EPC), v8 = *(const chunk_t*)(vr + q * EPC);
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
-      for (int e = 0; e < EPC; ++e) { w[q * EPC + e] = (float)w8[e]; v[q * EPC + e] = (float)v8[e]; }
+    for (int p = 0; p < CP / (2 * EPC); ++p) {
+      const u32x4 r8 = *(const u32x4*)(&rdT[row][p * 2 * EPC + half * EPC]);
+      const u32x4 d8 = *(const u32x4*)(&dlT[row][p * 2 * EPC + half * EPC]);
+      MfmaChunk<T>::run(r8, w3[p], acc);
+      MfmaChunk<T>::run(d8, v3[p], acc);
     }
-    float out[S];
+    // registers 0..3 of lanes 0..31: samples i0..i0+3 of column jb + lane
+    if (j_ok) {
+      float out[S];
 #pragma unroll
-    for (int ss = 0; ss < S; ++ss) {
-      const int ii = i0 + ss;
-      float o = 0.f;
-      if (ii < a.B) {
-        float back = 0.f;
-#pragma unroll
-        for (int cc = 0; cc < CP; ++cc) back += rd[ss][cc] * w[cc] + dl[ss][cc] * v[cc];
-        const long long f = (long long)ii * a.ldf + j;
-        o = back * a.dphi[f];
-        if (a.e2) o += a.e2[f] * a.Rz[f];
-        ((T*)a.RD)[(long long)ii * a.ldRD + j] = from_float<T>(o);
+      for (int ss = 0; ss < S; ++ss) {
+        const int ii = i0 + ss;
+        float o = 0.f;
+        if (ii < a.B) {
+          o = acc[ss] * dphi3[ss] + e23[ss] * rz3[ss];
+          ((T*)a.RD)[(long long)ii * a.ldRD + j] = from_float<T>(o);
+        }
+        out[ss] = o;                                       // rows beyond the batch: zero padding
       }
-      out[ss] = o;                                       // rows beyond the batch: zero padding
-    }
-    T* ot = (T*)a.RDt + (long long)j * a.ldRDt + i0;
+      T* ot = (T*)a.RDt + (long long)j * a.ldRDt + i0;
 #pragma unroll
-    for (int ss = 0; ss < S; ++ss) ot[ss] = from_float<T>(out[ss]);
+      for (int ss = 0; ss < S; ++ss) ot[ss] = from_float<T>(out[ss]);
+    }
   }
 }
 
@@ -380,11 +422,12 @@ void launch_last_layer_rop(Ctx& ctx, Elem elem, const LastRopArgs& a) {
   if (a.B <= 0) return;
   Launch l(ctx, BETTY_K_LOSS, 4.0 * a.B * a.n_in * a.C * 2.0, 0);
   const int blocks = (a.B + 3) / 4;
-  // enough column splits to occupy the chip, each at least one pass of the workgroup wide
-  int splits = std::max(1, std::min(256 / blocks, (a.n_in + 511) / 512 * 2));
+  // column splits: at most one block of 32 columns per wavefront (16 x 32 per workgroup), and
+  // enough workgroups to occupy the chip
+  const int splits = std::max((a.n_in + 511) / 512, std::max(1, std::min(256 / blocks, (a.n_in + 31) / 32)));
   const dim3 grid(blocks, splits);
-  if (elem == ELEM_BF16) last_layer_rop_kernel<__bf16><<<grid, 512, 0, ctx.stream>>>(a);
-  else last_layer_rop_kernel<float><<<grid, 512, 0, ctx.stream>>>(a);
+  if (elem == ELEM_BF16) last_layer_rop_kernel<__bf16><<<grid, 1024, 0, ctx.stream>>>(a);
+  else last_layer_rop_kernel<float><<<grid, 1024, 0, ctx.stream>>>(a);
 }
 
 void launch_loss_directional_rows(Ctx& ctx, int loss, const float* P, const float* Z, const int32_t* y,
