@@ -303,11 +303,11 @@ inline bool has_side(int mask, int side) { return (mask >> side) & 1; }
 
 // a_l, phi'(z_l) (and phi'' on the lower side), logits, per-sample loss, output delta
 void forward_and_loss(betty_handle h, OperandSet& os, int sides, const float* w, const float* theta,
-                      const float* omega_fixed = nullptr) {
+                      const float* omega_fixed = nullptr, bool skip_last = false) {
   const int L = h->L;
   const bool hybrid = hybrid_forward(h, os);
   OperandSet& fs = hybrid ? h->sets[1] : os;          // operands of the forward products
-  for (int l = 1; l <= L; ++l) {
+  for (int l = 1; l <= (skip_last ? L - 1 : L); ++l) {
     const LayerInfo& li = h->layers[l - 1];
     const bool last = l == L;
     GemmBatch b;
@@ -348,6 +348,7 @@ void forward_and_loss(betty_handle h, OperandSet& os, int sides, const float* w,
       launch_convert_batch(h->ctx, os.elem, cb);
     }
   }
+  if (skip_last) return;
   const LayerInfo& lo = h->layers[L - 1];
   LossBatch lb;
   for (int side = 0; side < 2; ++side) {
@@ -372,9 +373,9 @@ void forward_and_loss(betty_handle h, OperandSet& os, int sides, const float* w,
 }
 
 // delta_l for every layer below the output (and (delta W^T) phi'' on the lower side)
-void backward_chain(betty_handle h, OperandSet& os, int sides) {
+void backward_chain(betty_handle h, OperandSet& os, int sides, int l_from = 0) {
   const int L = h->L;
-  for (int l = L; l >= 2; --l) {
+  for (int l = l_from > 0 ? l_from : L; l >= 2; --l) {
     const LayerInfo& li = h->layers[l - 1];
     GemmBatch b;
     double flops = 0;
@@ -398,6 +399,45 @@ void backward_chain(betty_handle h, OperandSet& os, int sides) {
     }
     launch_gemm_batch(h->ctx, os.elem, plan_chain(h, os.elem, tiles128, li.n_out_p), b, flops);
   }
+}
+
+// Forward pass, loss and backward chain.  A narrow output layer (see LastGradArgs) goes through
+// one vector kernel that produces the logits, the loss quantities and delta_{L-1}.
+void forward_backward(betty_handle h, OperandSet& os, int sides, const float* w, const float* theta,
+                      const float* omega_fixed = nullptr) {
+  const int L = h->L;
+  const LayerInfo& lo = h->layers[L - 1];
+  const bool narrow = L >= 2 && lo.n_out <= LAST_ROP_MAX_C && !hybrid_forward(h, os);
+  if (!narrow) {
+    forward_and_loss(h, os, sides, w, theta, omega_fixed);
+    backward_chain(h, os, sides);
+    return;
+  }
+  forward_and_loss(h, os, sides, w, theta, omega_fixed, true);
+  LastGradArgs a{};
+  for (int side = 0; side < 2; ++side) {
+    if (!has_side(sides, side)) continue;
+    SideBuf& sb = os.side[side];
+    LastGradSide& d = a.side[a.n_sides++];
+    d.A = h->at<void>(sb.A[L - 1]); d.lda = lo.n_in_p;
+    d.y = h->batch[side].y; d.target = h->batch[side].target;
+    d.omega_fixed = side == 0 ? omega_fixed : nullptr;
+    d.ZL = h->f(sb.ZL); d.P = h->f(sb.P); d.ldz = lo.n_out_p;
+    d.ell = h->f(sb.ell); d.s = h->f(sb.s); d.omega = h->f(sb.omega);
+    d.DL = h->at<void>(sb.D[L]); d.DLt = h->at<void>(sb.Dt[L]); d.ldd = lo.n_out_p; d.ldDLt = sb.Bp;
+    d.dphi = h->f(sb.dphi[L - 1]); d.e2 = sb.e2[L - 1] ? h->f(sb.e2[L - 1]) : nullptr; d.ldf = lo.n_in_p;
+    d.D = h->at<void>(sb.D[L - 1]); d.ldD = lo.n_in_p; d.Dt = h->at<void>(sb.Dt[L - 1]); d.ldDt = sb.Bp;
+    d.B = sb.B;
+    d.reweight = (side == 0 && h->desc.hp == BETTY_HP_REWEIGHT_NET) ? 1 : 0;
+    d.inv_batch = 1.0f / (float)sb.B;
+  }
+  a.Wt = h->at<void>(os.Wt[L - 1]); a.ldt = lo.n_in_p;
+  a.Wn = h->at<void>(os.Wn[L - 1]); a.ldn = lo.n_out_p;
+  a.bias = h->desc.has_bias ? w + lo.b_off : nullptr;
+  a.theta = theta; a.hidden = h->desc.wnet_hidden;
+  a.n_in = lo.n_in; a.n_in_p = lo.n_in_p; a.C = lo.n_out; a.loss = h->desc.loss;
+  launch_last_layer_grad(h->ctx, os.elem, a);
+  backward_chain(h, os, sides, L - 1);
 }
 
 // What the grouped weight-gradient launch does with its result.
@@ -600,8 +640,7 @@ void lower_grad_seq(betty_handle h, OperandSet& os, const float* w, const float*
     launch_diff(h->ctx, w, lam, h->f(h->vec_g), h->d);
     x = h->f(h->vec_g);
   }
-  forward_and_loss(h, os, SIDE_TRAIN, w, wnet_theta(h, lam), omega_fixed);
-  backward_chain(h, os, SIDE_TRAIN);
+  forward_backward(h, os, SIDE_TRAIN, w, wnet_theta(h, lam), omega_fixed);
   WgradSink k{EPI_WGRAD, grad, dl, dl ? x : nullptr, nullptr, nullptr, 0.f, false};
   wgrad_batch(h, os, 0, false, k);
   if (loss_or_null) {
@@ -620,8 +659,7 @@ void lower_grad_seq(betty_handle h, OperandSet& os, const float* w, const float*
 void upper_grad_seq(betty_handle h, OperandSet& os, const float* w, const float* lam, bool with_lower,
                     const WgradSink& sink, float* loss_or_null) {
   const int sides = with_lower ? SIDE_BOTH : SIDE_VAL;
-  forward_and_loss(h, os, sides, w, wnet_theta(h, lam));
-  backward_chain(h, os, sides);
+  forward_backward(h, os, sides, w, wnet_theta(h, lam));
   wgrad_batch(h, os, 1, false, sink);
   if (loss_or_null)
     launch_weighted_loss_sum(h->ctx, h->f(os.side[1].s), h->f(os.side[1].ell), os.side[1].B, nullptr, loss_or_null);
@@ -629,8 +667,7 @@ void upper_grad_seq(betty_handle h, OperandSet& os, const float* w, const float*
 
 // forward/backward cache of the train batch for the R-op passes (no parameter gradient)
 void prepare_lower(betty_handle h, OperandSet& os, const float* w, const float* lam) {
-  forward_and_loss(h, os, SIDE_TRAIN, w, wnet_theta(h, lam));
-  backward_chain(h, os, SIDE_TRAIN);
+  forward_backward(h, os, SIDE_TRAIN, w, wnet_theta(h, lam));
 }
 
 // out = -(1/B) sum_i c_i dR/dtheta with c_i = <grad_w l_i, scale * qflat>
@@ -1141,8 +1178,7 @@ betty_status betty_lower_sgd_step(betty_handle h, float* w, const float* lambda,
   const bool prox = h->desc.hp == BETTY_HP_PROXIMAL;
   const float* dl = diag_log(h, lambda);
   make_weight_operands(h, os, w);
-  forward_and_loss(h, os, SIDE_TRAIN, w, wnet_theta(h, lambda));
-  backward_chain(h, os, SIDE_TRAIN);
+  forward_backward(h, os, SIDE_TRAIN, w, wnet_theta(h, lambda));
   if (loss_or_null) {                      // the cost at the w before the step
     float* add = nullptr;
     if (dl) {

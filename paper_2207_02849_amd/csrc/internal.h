@@ -193,6 +193,30 @@ struct LastRopArgs {
 constexpr int LAST_ROP_MAX_C = 16;
 void launch_last_layer_rop(Ctx&, Elem, const LastRopArgs&);
 
+// The first-order counterpart for narrow outputs: logits z_L = a_{L-1} W_L + b_L, per-sample loss,
+// sample weight and output delta (what loss_rows_kernel computes), and
+// delta_{L-1} = (delta_L W_L^T) .* phi'(z_{L-1}) (with e2 <- (delta_L W_L^T) .* e2 in place when e2
+// is given), for up to two batches (train, validation) in one launch.
+struct LastGradSide {
+  const void* A; int lda;                        // a_{L-1} [B][lda], operand type
+  const int32_t* y; const float* target;         // labels, or targets [B][C]
+  const float* omega_fixed;                      // sample weights to use instead of the weight net, or null
+  float* ZL; float* P; int ldz;                  // out: logits, softmax probabilities, fp32 [B][ldz]
+  float* ell; float* s; float* omega;            // out: per-sample loss, scale, weight
+  void* DL; void* DLt; int ldd, ldDLt;           // out: delta_L [B][ldd] and [n_out_p][ldDLt]
+  const float* dphi; float* e2; int ldf;         // layer L-1, fp32 [B][ldf]
+  void* D; int ldD; void* Dt; int ldDt;          // out: delta_{L-1} [B][ldD] and [n_in_p][ldDt]
+  int B, reweight; float inv_batch;
+};
+struct LastGradArgs {
+  LastGradSide side[2]; int n_sides;
+  const void* Wt; int ldt; const void* Wn; int ldn;   // W_L as [n_out_p][n_in_p] and [n_in_p][n_out_p]
+  const float* bias;                                  // b_L (fp32), or null
+  const float* theta; int hidden;                     // weight net (sides with reweight set)
+  int n_in, n_in_p, C, loss;
+};
+void launch_last_layer_grad(Ctx&, Elem, const LastGradArgs&);
+
 void launch_loss_hessian_rows(Ctx&, Elem, int loss, const float* P, const float* Rz, long long ld,
                               const float* s, int rows, int C, void* D, int ldD, void* Dt, int ldDt);
 // c_i = < dl_i/dz, Rz_i >

@@ -430,6 +430,182 @@ void launch_last_layer_rop(Ctx& ctx, Elem elem, const LastRopArgs& a) {
   else last_layer_rop_kernel<float><<<grid, 1024, 0, ctx.stream>>>(a);
 }
 
+// Same layout as last_layer_rop_kernel (16 wavefronts, 4 samples, zero-padded MFMA blocks);
+// blockIdx.z selects the batch.
+template <typename T>
+__global__ __launch_bounds__(1024) void last_layer_grad_kernel(LastGradArgs a) {
+  constexpr int S = 4, CP = LAST_ROP_MAX_C, EPC = 16 / (int)sizeof(T), NW = 16, U = sizeof(T) == 4 ? 2 : 4;
+  __shared__ float part[NW][S * CP];
+  __shared__ __attribute__((aligned(16))) T dlT[32][CP];   // rows >= S stay zero
+  const LastGradSide& sd = a.side[blockIdx.z];
+  const int t = threadIdx.x, lane = t & 63, ks = t >> 6;
+  const int row = lane & 31, half = lane >> 5;
+  const int i0 = blockIdx.x * S;
+  if (i0 >= sd.B) return;                                   // the two batches may differ in size
+  const int jsplit = ((a.n_in + gridDim.y - 1) / gridDim.y + 31) / 32 * 32;
+  const int j_begin = blockIdx.y * jsplit, j_end = min(a.n_in, j_begin + jsplit);
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  for (int x = t; x < 32 * CP; x += 64 * NW) (&dlT[0][0])[x] = from_float<T>(0.f);
+
+  // inputs of phase 3 that do not depend on the earlier phases
+  const int jb = j_begin + ks * 32;
+  const bool jb_ok = jb < j_end;
+  const int j = jb + lane;
+  const bool j_ok = jb_ok && lane < 32 && j < j_end;
+  u32x4 w3[CP / (2 * EPC)];
+  float dphi3[S], e23[S];
+#pragma unroll
+  for (int p = 0; p < CP / (2 * EPC); ++p) w3[p] = zero;
+#pragma unroll
+  for (int ss = 0; ss < S; ++ss) { dphi3[ss] = 0.f; e23[ss] = 0.f; }
+  if (jb_ok) {
+    const T* wr = (const T*)a.Wn + (long long)(jb + row) * a.ldn + half * EPC;
+#pragma unroll
+    for (int p = 0; p < CP / (2 * EPC); ++p) w3[p] = *(const u32x4*)(wr + p * 2 * EPC);
+  }
+  if (j_ok) {
+#pragma unroll
+    for (int ss = 0; ss < S; ++ss)
+      if (i0 + ss < sd.B) {
+        const long long f = (long long)(i0 + ss) * sd.ldf + j;
+        dphi3[ss] = sd.dphi[f];
+        if (sd.e2) e23[ss] = sd.e2[f];
+      }
+  }
+
+  // ---- phase 1: logits block (4 x C), K = n_in sliced over the wavefronts
+  {
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    const bool a_ok = row < S && i0 + row < sd.B, b_ok = row < a.C;
+    const int pairs = a.n_in_p / (2 * EPC), per = (pairs + NW - 1) / NW;
+    const int p_begin = ks * per, p_end = min(pairs, p_begin + per);
+    const T* av = (const T*)sd.A + (long long)(i0 + row) * sd.lda + half * EPC;
+    const T* w = (const T*)a.Wt + (long long)row * a.ldt + half * EPC;
+    for (int p0 = p_begin; p0 < p_end; p0 += U) {
+      u32x4 a8[U], w8[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) { a8[u] = zero; w8[u] = zero; }
+      if (a_ok) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (p0 + u < p_end) a8[u] = *(const u32x4*)(av + (p0 + u) * 2 * EPC);
+      }
+      if (b_ok) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (p0 + u < p_end) w8[u] = *(const u32x4*)(w + (p0 + u) * 2 * EPC);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) MfmaChunk<T>::run(a8[u], w8[u], acc);
+    }
+    if (lane < CP) {
+#pragma unroll
+      for (int r = 0; r < S; ++r) part[ks][r * CP + lane] = acc[r];
+    }
+  }
+  __syncthreads();
+
+  // ---- phase 2: 16 lanes per sample (lane % 16 = class)
+  if (ks == 0) {
+    const int s = lane >> 4, c = lane & 15, i = i0 + s;
+    const bool iok = i < sd.B, ok = iok && c < a.C;
+    float z = 0.f;
+#pragma unroll
+    for (int q = 0; q < NW; ++q) z += part[q][lane];
+    if (ok && a.bias) z += a.bias[c];
+    float ell, p = 0.f, dz;
+    int y = 0;
+    if (a.loss == BETTY_LOSS_SOFTMAX_CE) {
+      float m = ok ? z : -INFINITY;
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+      const float ex = ok ? expf(z - m) : 0.f;
+      float sum = ex;
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+      y = iok ? sd.y[i] : 0;
+      const int yy = min(max(y, 0), a.C - 1);
+      const float zy = __shfl(z, (lane & ~15) + yy, 64);
+      ell = logf(sum) + m - zy;
+      p = ex / sum;
+      dz = p - (c == y ? 1.f : 0.f);
+    } else {
+      const float r = ok ? z - sd.target[(long long)i * a.C + c] : 0.f;
+      float acc2 = r * r;
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) acc2 += __shfl_xor(acc2, o, 64);
+      ell = acc2;
+      dz = 2.f * r;
+    }
+    float omega = 1.f;
+    if (sd.reweight && sd.omega_fixed) {
+      omega = iok ? sd.omega_fixed[i] : 1.f;
+    } else if (sd.reweight) {
+      const int H = a.hidden;
+      float pw = 0.f;
+      for (int hj = c; hj < H; hj += 16) pw += a.theta[2 * H + hj] * fmaxf(a.theta[hj] * ell + a.theta[H + hj], 0.f);
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) pw += __shfl_xor(pw, o, 64);
+      omega = 1.f / (1.f + expf(-(pw + a.theta[3 * H])));
+    }
+    const float sc = omega * sd.inv_batch;
+    const T dv = from_float<T>(sc * dz);
+    if (ok) dlT[s][c] = dv;
+    if (blockIdx.y == 0) {
+      if (iok && c == 0) { sd.ell[i] = ell; sd.s[i] = sc; sd.omega[i] = omega; }
+      if (ok) {
+        sd.ZL[(long long)i * sd.ldz + c] = z;
+        if (a.loss == BETTY_LOSS_SOFTMAX_CE) sd.P[(long long)i * sd.ldz + c] = p;
+        ((T*)sd.DL)[(long long)i * sd.ldd + c] = dv;
+        ((T*)sd.DLt)[(long long)c * sd.ldDLt + i] = dv;
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- phase 3: delta_{L-1} for 32 columns per wavefront
+  if (jb_ok) {
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+    for (int p = 0; p < CP / (2 * EPC); ++p) {
+      const u32x4 d8 = *(const u32x4*)(&dlT[row][p * 2 * EPC + half * EPC]);
+      MfmaChunk<T>::run(d8, w3[p], acc);
+    }
+    if (j_ok) {
+      float out[S];
+#pragma unroll
+      for (int ss = 0; ss < S; ++ss) {
+        const int ii = i0 + ss;
+        float o = 0.f;
+        if (ii < sd.B) {
+          o = acc[ss] * dphi3[ss];
+          ((T*)sd.D)[(long long)ii * sd.ldD + j] = from_float<T>(o);
+          if (sd.e2) sd.e2[(long long)ii * sd.ldf + j] = acc[ss] * e23[ss];
+        }
+        out[ss] = o;
+      }
+      T* ot = (T*)sd.Dt + (long long)j * sd.ldDt + i0;
+#pragma unroll
+      for (int ss = 0; ss < S; ++ss) ot[ss] = from_float<T>(out[ss]);
+    }
+  }
+}
+
+void launch_last_layer_grad(Ctx& ctx, Elem elem, const LastGradArgs& a) {
+  int blocks = 0;
+  for (int i = 0; i < a.n_sides; ++i) blocks = std::max(blocks, (a.side[i].B + 3) / 4);
+  if (blocks <= 0) return;
+  Launch l(ctx, BETTY_K_LOSS);
+  const int splits = std::max((a.n_in + 511) / 512, std::max(1, std::min(256 / (blocks * a.n_sides), (a.n_in + 31) / 32)));
+  const dim3 grid(blocks, splits, a.n_sides);
+  if (elem == ELEM_BF16) last_layer_grad_kernel<__bf16><<<grid, 1024, 0, ctx.stream>>>(a);
+  else last_layer_grad_kernel<float><<<grid, 1024, 0, ctx.stream>>>(a);
+}
+
 void launch_loss_directional_rows(Ctx& ctx, int loss, const float* P, const float* Z, const int32_t* y,
                                   const float* target, const float* Rz, long long ld, int rows, int C,
                                   float* c) {
