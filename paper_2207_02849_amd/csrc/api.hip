@@ -407,7 +407,9 @@ void forward_backward(betty_handle h, OperandSet& os, int sides, const float* w,
                       const float* omega_fixed = nullptr) {
   const int L = h->L;
   const LayerInfo& lo = h->layers[L - 1];
-  const bool narrow = L >= 2 && lo.n_out <= LAST_ROP_MAX_C && !hybrid_forward(h, os);
+  // (also with the fp32 forward of ReLU networks: the output layer has no mask to protect, and the
+  // operand-type copy of a_{L-1} exists either way)
+  const bool narrow = L >= 2 && lo.n_out <= LAST_ROP_MAX_C;
   if (!narrow) {
     forward_and_loss(h, os, sides, w, theta, omega_fixed);
     backward_chain(h, os, sides);
