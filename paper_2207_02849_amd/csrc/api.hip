@@ -242,6 +242,7 @@ void set_pairs(GemmArgs& g, const void* A0, int lda0, const void* B0, int ldb0, 
   g.A[0] = A0; g.B[0] = B0; g.lda[0] = lda0; g.ldb[0] = ldb0; g.Kp[0] = K0p;
   g.A[1] = A1 ? A1 : A0; g.B[1] = A1 ? B1 : B0; g.lda[1] = A1 ? lda1 : lda0; g.ldb[1] = A1 ? ldb1 : ldb0;
   g.Kp[1] = A1 ? K1p : 0;
+  g.xgm = g.xgn = 0;
 }
 
 // one activation-shaped GEMM with a fused epilogue
@@ -442,6 +443,22 @@ void forward_backward(betty_handle h, OperandSet& os, int sides, const float* w,
   backward_chain(h, os, sides, L - 1);
 }
 
+// Split of a tile grid over the eight XCDs (see GemmArgs::xgm): the factorisation gm x gn = 8 that
+// divides the grid and minimises the operand rows each L2 fetches, gn * tiles_m + gm * tiles_n
+// (every XCD reads tiles_m / gm row panels and tiles_n / gn column panels).  gm = gn = 0 when
+// nothing fits or the row-major order is already as good.
+void xcd_split(int tiles_m, int tiles_n, int& gm, int& gn) {
+  gm = gn = 0;
+  if ((tiles_m * tiles_n) % 8 != 0 || tiles_m * tiles_n < 256) return;   // small grids: no measurable gain
+  long best = tiles_n % 8 == 0 ? 8L * tiles_m + tiles_n : -1;      // row-major order = 1 x 8 when tiles_n % 8 == 0
+  for (int a = 1; a <= 8; a *= 2) {
+    const int b = 8 / a;
+    if (tiles_m % a || tiles_n % b) continue;
+    const long cost = (long)b * tiles_m + (long)a * tiles_n;
+    if (best < 0 || cost < best) { best = cost; gm = a; gn = b; }
+  }
+}
+
 // What the grouped weight-gradient launch does with its result.
 struct WgradSink {
   int mode;                 // EPI_WGRAD / EPI_WGRAD_INIT / EPI_WGRAD_NEUMANN
@@ -484,6 +501,7 @@ void wgrad_batch(betty_handle h, OperandSet& os, int side, bool rop, const Wgrad
         flops += 4.0 * B * li.n_in * li.n_out;
       }
       p.g.M = li.n_in; p.g.N = li.n_out; p.g.Mp = li.n_in_p; p.g.Np = li.n_out_p;
+      xcd_split(li.n_in_p / gemm_cfg_tile(h->tune_wgrad_cfg), li.n_out_p / gemm_cfg_tile(h->tune_wgrad_cfg), p.g.xgm, p.g.xgn);
       Epilogue e = blank_epilogue(k.mode);
       e.ldc = li.n_out;
       e.C = k.C ? k.C + li.w_off : nullptr;

@@ -371,7 +371,14 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
   const GemmArgs& g = batch.p[pi].g;
   const int tile = bid - batch.block_begin[pi];
   const int tiles_n = g.Np / BN;
-  const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+  int tm = tile / tiles_n, tn = tile % tiles_n;
+  if (g.xgm > 0) {                                 // XCD-compact order (see GemmArgs)
+    const int x = tile & 7, q = tile >> 3;
+    const int rm = (g.Mp / BM) / g.xgm, rn = tiles_n / g.xgn;
+    tm = (x / g.xgn) * rm + q / rn;
+    tn = (x % g.xgn) * rn + q % rn;
+  }
+  const int m0 = tm * BM, n0 = tn * BN;
 
   const int T0 = g.Kp[0] / KT, T1 = g.Kp[1] / KT, TT = T0 + T1;
   const int NI = (TT + KG - 1) / KG;               // iterations of every group (same barrier count)

@@ -30,6 +30,10 @@ struct GemmArgs {
   int Kp[2];                 // padded reduction extents in elements; 0 = pair absent
   int M, N;                  // valid output extent (epilogue stores are bounds-checked against it)
   int Mp, Np;                // padded extents (define the tile grid)
+  // Workgroups go to the eight XCDs round-robin, so tiles t, t+8, t+16, ... of a problem share an
+  // L2.  With xgm x xgn = 8 those tiles are laid out as one compact (tiles_m/xgm) x (tiles_n/xgn)
+  // rectangle, which cuts the operand panels each L2 has to fetch; 0 = row-major tile order.
+  int xgm, xgn;
 };
 
 // What happens to a finished accumulator tile.
