@@ -10,11 +10,15 @@ train/val batches of 256, K = 5, alpha = 0.01.  Inputs are synthetic (seeded Gau
 mixture) and resident in HBM before the timed region.
 
 Prints one JSON line.  Besides the contract keys it carries
-  roofline      the dominant kernel (the fused MFMA GEMM, which also carries the Neumann
-                update in its epilogue) against the bf16 MFMA peak, from HIP events recorded
-                by the library around every launch
-  cpu_baseline  the fp64 numpy oracle timed on the host cores for the same workload
-and, for context, the finite-difference variant's rate and the per-HVP figures.
+  roofline        the kernel at the top of the rocprofv3 trace: the weight-gradient instantiation of
+                  the fused GEMM whose epilogue applies one step of the Neumann sum to the parameter-
+                  sized vectors.  It is bandwidth-bound (K = batch = 256): algorithmic bytes per
+                  launch (20 per parameter) over the launch duration from HIP events recorded by the
+                  library, against the HBM peak
+  gemm_aggregate  every launch of the GEMM kernel template against the bf16 MFMA peak
+  hvp             the per-Hessian-vector-product figures of the metric
+  cpu_baseline    the fp64 numpy oracle timed on the host cores for the same workload
+and, for context, the finite-difference, bilevel-step and three-level-chain rates.
 """
 import argparse
 import json
@@ -37,11 +41,12 @@ def algorithmic_flops(dims, B):
     return 6.0 * B * P - 2.0 * B * first, 12.0 * B * P - 8.0 * B * first
 
 
-def pmc_traffic_bytes_per_launch(config):
-    """HBM-side bytes per GEMM launch from the committed counter summary, or None when there is no
-    summary for this workload or the kernel sources have changed since it was taken."""
+def pmc_traffic_bytes_per_launch(config, which="gemm_fused_kernel"):
+    """HBM-side bytes per launch from a committed counter summary (all GEMM launches, or the
+    weight-gradient/Neumann instantiation alone), or None when there is no summary for this
+    workload or the kernel sources have changed since it was taken."""
     from paper_2207_02849_amd import profile_summary
-    path = os.path.join(ROOT, "profiles", f"gemm_fused_kernel_config{config}_pmc.txt")
+    path = os.path.join(ROOT, "profiles", f"{which}_config{config}_pmc.txt")
     if not os.path.exists(path):
         return None
     fields = {}
@@ -166,15 +171,17 @@ def main():
         a[0] += 1; a[1] += ms; a[2] += flops; a[3] += nbytes
     # every launch of the GEMM kernel, whether its epilogue carries the Neumann update or not
     upd = by_kind.get("gemm_update", [0, 0.0, 0.0, 0.0])
+    fin = by_kind.get("gemm_update_final", [0, 0.0, 0.0, 0.0])
     plain = by_kind.get("gemm", [0, 0.0, 0.0, 0.0])
-    gemm = [plain[i] + upd[i] for i in range(4)]
+    gemm = [plain[i] + upd[i] + fin[i] for i in range(4)]
     gemm_tflops = gemm[2] / (gemm[1] * 1e-3) / 1e12
     # vector phase of the recurrence: it lives in the epilogue of the weight-gradient launch, so its
     # rate is quoted over the whole fused launch (20 algorithmic bytes per parameter)
     vec_gbs = upd[3] / (upd[1] * 1e-3) / 1e9 if upd[1] > 0 else 0.0
     phases = {k: {"launches_per_step": v[0] / n_prof, "ms_per_step": v[1] / n_prof} for k, v in by_kind.items()}
 
-    traffic = pmc_traffic_bytes_per_launch(args.config)
+    traffic_all = pmc_traffic_bytes_per_launch(args.config)
+    traffic_upd = pmc_traffic_bytes_per_launch(args.config, "gemm_fused_kernel_wgrad_neumann")
     result = {
         "metric": "hypergradients/s, MLP Neumann K=5; HVP % of MFMA peak",
         "value": 1.0 / t_step,
@@ -191,22 +198,33 @@ def main():
         "config": {"workload": f"config {args.config}: {wl.name}, d={wl.d}, batch {B}/{wl.X_val.shape[0]}, "
                                f"Neumann K={K} alpha={alpha}"},
         "roofline": {
+            "bound": "hbm",
+            "kernel": "gemm_fused_kernel<64x64 tile, epilogue WGRAD_NEUMANN>: all layers' weight-gradient "
+                      "products of one Hessian-vector product with the Neumann step on s, g, lambda and "
+                      "the operand copies in the epilogue (top kernel of the trace)",
+            "achieved": vec_gbs,
+            "peak": PEAK_HBM_GBS,
+            "unit": "GB/s",
+            "frac": vec_gbs / PEAK_HBM_GBS,
+            "traffic": traffic_upd,
+            "launches_per_step": upd[0] / n_prof,
+            "avg_launch_us": (upd[1] / upd[0] * 1e3) if upd[0] else None,
+            "algorithmic_bytes_per_launch": (upd[3] / upd[0]) if upd[0] else None,
+        },
+        "gemm_aggregate": {
             "bound": "mfma",
             "kernel": "gemm_fused_kernel (all instantiations; every GEMM launch of one hypergradient)",
             "achieved": gemm_tflops,
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",
             "frac": gemm_tflops / PEAK_BF16_TFLOPS,
-            "traffic": traffic,
+            "traffic": traffic_all,
             "launches_per_step": gemm[0] / n_prof,
             "avg_launch_us": gemm[1] / gemm[0] * 1e3,
             "avg_launch_gflop": gemm[2] / gemm[0] / 1e9,
         },
         "hvp": {"ms": t_hvp * 1e3, "algorithmic_gflop": hvp_flops / 1e9,
                 "tflops": hvp_flops / t_hvp / 1e12, "frac_of_bf16_mfma_peak": hvp_flops / t_hvp / 1e12 / PEAK_BF16_TFLOPS},
-        "neumann_update": {"where": "epilogue of the grouped weight-gradient GEMM launch",
-                           "achieved_gbs": vec_gbs, "frac_of_hbm_peak": vec_gbs / PEAK_HBM_GBS,
-                           "avg_launch_us": (upd[1] / upd[0] * 1e3) if upd[0] else None},
         "phases": phases,
         "fd_hypergradients_per_s": (1.0 / t_fd) if t_fd else None,
         "bilevel_upper_steps_per_s": {"value": 1.0 / t_bilevel,

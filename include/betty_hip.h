@@ -219,8 +219,12 @@ typedef struct {
 enum {
   BETTY_K_GEMM = 0, BETTY_K_EPILOGUE = 1, BETTY_K_LOSS = 2, BETTY_K_SHADOW = 3,
   BETTY_K_VECTOR = 4, BETTY_K_REDUCE = 5, BETTY_K_WNET = 6, BETTY_K_OTHER = 7,
-  BETTY_K_GEMM_UPDATE = 8   /* weight-gradient GEMM whose epilogue applies the Neumann update:
-                               flops = its 2MNK, bytes = 20 per parameter (v, p, lambda read; v, p written) */
+  BETTY_K_GEMM_UPDATE = 8,  /* weight-gradient GEMM whose epilogue applies one step of the Neumann sum:
+                               flops = its 2MNK, bytes = per parameter s, g (and the diagonal) read,
+                               s and two operand-type copies written (20 with a diagonal term)        */
+  BETTY_K_GEMM_UPDATE_FINAL = 9,  /* the same for the last step of the L2-decay kind, which writes
+                               d(lambda) only (s, g, lambda, w read: 20 bytes per parameter)         */
+  BETTY_K_LAST_LAYER = 10   /* the narrow-output-layer kernels (flops = their products)              */
 };
 
 /* While enabled, every kernel launch of the handle is bracketed by HIP events on the

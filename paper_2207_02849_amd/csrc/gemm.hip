@@ -636,8 +636,9 @@ void launch_gemm_batch(Ctx& ctx, Elem elem, int cfg, GemmBatch& b, double flops,
   const int total = blocks + bias_blocks;
   if (total <= 0) return;
   const int mode0 = b.p[0].e.mode;
-  const bool update = mode0 == EPI_WGRAD_NEUMANN || mode0 == EPI_WGRAD_NEUMANN_L2;
-  Launch l(ctx, update ? BETTY_K_GEMM_UPDATE : BETTY_K_GEMM, flops, bytes);
+  const int kind = mode0 == EPI_WGRAD_NEUMANN ? BETTY_K_GEMM_UPDATE
+                 : mode0 == EPI_WGRAD_NEUMANN_L2 ? BETTY_K_GEMM_UPDATE_FINAL : BETTY_K_GEMM;
+  Launch l(ctx, kind, flops, bytes);
   hipError_t err = hipSuccess;
   if (elem == ELEM_BF16) launch_elem<__bf16>(cfg, b.p[0].e.mode, total, ctx.stream, b, err);
   else launch_elem<float>(cfg, b.p[0].e.mode, total, ctx.stream, b, err);

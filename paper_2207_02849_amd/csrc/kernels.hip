@@ -420,7 +420,7 @@ __global__ __launch_bounds__(1024) void last_layer_rop_kernel(LastRopArgs a) {
 
 void launch_last_layer_rop(Ctx& ctx, Elem elem, const LastRopArgs& a) {
   if (a.B <= 0) return;
-  Launch l(ctx, BETTY_K_LOSS, 4.0 * a.B * a.n_in * a.C * 2.0, 0);
+  Launch l(ctx, BETTY_K_LAST_LAYER, 8.0 * a.B * a.n_in * a.C, 0);      // two pairs in each of two products
   const int blocks = (a.B + 3) / 4;
   // column splits: at most one block of 32 columns per wavefront (16 x 32 per workgroup), and
   // enough workgroups to occupy the chip
@@ -599,7 +599,9 @@ void launch_last_layer_grad(Ctx& ctx, Elem elem, const LastGradArgs& a) {
   int blocks = 0;
   for (int i = 0; i < a.n_sides; ++i) blocks = std::max(blocks, (a.side[i].B + 3) / 4);
   if (blocks <= 0) return;
-  Launch l(ctx, BETTY_K_LOSS);
+  double flops = 0;
+  for (int i = 0; i < a.n_sides; ++i) flops += 4.0 * a.side[i].B * a.n_in * a.C;
+  Launch l(ctx, BETTY_K_LAST_LAYER, flops, 0);
   const int splits = std::max((a.n_in + 511) / 512, std::max(1, std::min(256 / (blocks * a.n_sides), (a.n_in + 31) / 32)));
   const dim3 grid(blocks, splits, a.n_sides);
   if (elem == ELEM_BF16) last_layer_grad_kernel<__bf16><<<grid, 1024, 0, ctx.stream>>>(a);
