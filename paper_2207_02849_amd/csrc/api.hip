@@ -332,22 +332,13 @@ void forward_and_loss(betty_handle h, OperandSet& os, int sides, const float* w,
         e.d2_out = sb.e2[l] ? h->f(sb.e2[l]) : nullptr;
         e.out = h->at<void>(fb.A[l]); e.ld = li.n_out_p;
         e.outT = hybrid ? nullptr : h->at<void>(fb.At[l]); e.ldT = sb.Bp;
+        if (hybrid) { e.out2 = h->at<void>(sb.A[l]); e.outT2 = h->at<void>(sb.At[l]); }
       }
       p.e = e;
       flops += 2.0 * sb.B * li.n_in * li.n_out;
       tiles128 += (sb.Bp / 128) * (li.n_out_p / 128);
     }
     launch_gemm_batch(h->ctx, fs.elem, plan_chain(h, fs.elem, tiles128, li.n_in_p), b, flops);
-    if (hybrid && !last) {
-      ConvertBatch cb;
-      for (int side = 0; side < 2; ++side) {
-        if (!has_side(sides, side)) continue;
-        SideBuf& sb = os.side[side];
-        cb.j[cb.n++] = ConvertJob{h->f(fs.side[side].A[l]), li.n_out_p, 1.f, sb.B, li.n_out,
-                                  h->at<void>(sb.A[l]), li.n_out_p, h->at<void>(sb.At[l]), sb.Bp};
-      }
-      launch_convert_batch(h->ctx, os.elem, cb);
-    }
   }
   if (skip_last) return;
   const LayerInfo& lo = h->layers[L - 1];

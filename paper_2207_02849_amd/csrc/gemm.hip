@@ -269,6 +269,23 @@ __device__ __forceinline__ void epi_finish(const Epilogue& e, int M, int N, int 
       if (rb + 8 * q < M) store4<T>(o + 8 * q, quad);
     }
   }
+  if constexpr (MODE == EPI_FWD && sizeof(T) == 4) {
+    // fp32 forward of a bf16 problem: the bf16 operand copies of the activation leave from here too
+    if (e.out2) {
+      __bf16* o = (__bf16*)e.out2;
+#pragma unroll
+      for (int k = 0; k < NR; ++k)
+        if (ok[k]) store1<__bf16>(o + (long long)epi_row<NR>(rb, k) * e.ld + col, val[k]);
+    }
+    if (e.outT2) {
+      __bf16* o = (__bf16*)e.outT2 + (long long)col * e.ldT + rb;
+#pragma unroll
+      for (int q = 0; q < NR / 4; ++q) {
+        const float quad[4] = {val[4 * q], val[4 * q + 1], val[4 * q + 2], val[4 * q + 3]};
+        if (rb + 8 * q < M) store4<__bf16>(o + 8 * q, quad);
+      }
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------

@@ -70,6 +70,7 @@ struct Epilogue {
   long long ldf;
   void* out; int ld;                     // operand-typed, row-major [row][col]
   void* outT; int ldT;                   // operand-typed, transposed [col][row]
+  void* out2; void* outT2;               // EPI_FWD only: further copies of `out` in bf16 (same ld, ldT), or null
   float* C; long long ldc;               // fp32 row-major (flat parameter slice for the WGRAD modes)
   const float* lam; const float* x;      // same indexing as C
   float* v; float* p; float alpha, beta, gamma;
