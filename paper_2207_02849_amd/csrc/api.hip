@@ -683,12 +683,12 @@ void prepare_lower(betty_handle h, OperandSet& os, const float* w, const float* 
 
 // out = -(1/B) sum_i c_i dR/dtheta with c_i = <grad_w l_i, scale * qflat>
 void mixed_reweight_seq(betty_handle h, OperandSet& os, const float* lam, const float* qflat, float scale,
-                        float* out) {
+                        float* out, bool copies_current = false) {
   SideBuf& sb = os.side[0];
   const int L = h->L;
   const LayerInfo& lo = h->layers[L - 1];
   // c_i is linear in the direction, so the scale is applied once, to the final sum over samples
-  make_shadows(h, os, qflat, 1.f, nullptr, &os.Vt);
+  if (!copies_current) make_shadows(h, os, qflat, 1.f, nullptr, &os.Vt);   // else os.Vt already holds qflat
   r_forward(h, os, qflat);
   launch_loss_directional_rows(h->ctx, h->desc.loss, h->f(sb.P), h->f(sb.ZL), h->batch[0].y,
                                h->batch[0].target, h->f(os.Rz[L]), lo.n_out_p, sb.B, lo.n_out, h->f(os.cvec));
@@ -815,12 +815,14 @@ static void neumann_seq(betty_handle h, const float* w, const float* lambda, con
   const float* g = u_or_null;
   const bool need_lower = K > 0 || rw;      // forward/backward cache of the train batch
   make_weight_operands(h, os, w);
+  // the reweighting mixed term runs one more R-forward along the final sum: its operand copies are
+  // written by whichever launch produces that sum
   if (u_or_null) {
     if (need_lower) prepare_lower(h, os, w, lambda);
-    if (K > 0) make_shadows(h, os, u_or_null, 1.f, &os.Vn, &os.Vt);
+    if (K > 0 || rw) make_shadows(h, os, u_or_null, 1.f, &os.Vn, &os.Vt);
   } else {
     // g = grad_w L_U lands in vec_v, with its operand copies for the first product
-    WgradSink init{EPI_WGRAD_INIT, nullptr, nullptr, nullptr, h->f(h->vec_v), nullptr, 0.f, K > 0};
+    WgradSink init{EPI_WGRAD_INIT, nullptr, nullptr, nullptr, h->f(h->vec_v), nullptr, 0.f, K > 0 || rw};
     upper_grad_seq(h, os, w, lambda, need_lower, init, nullptr);
     g = h->f(h->vec_v);
   }
@@ -836,17 +838,17 @@ static void neumann_seq(betty_handle h, const float* w, const float* lambda, con
       WgradSink fin{EPI_WGRAD_NEUMANN_L2, out, lambda, w, const_cast<float*>(g), const_cast<float*>(s_cur), alpha, false};
       hvp_cached(h, os, s_cur, fin, pipe);
     } else {
-      WgradSink step{EPI_WGRAD_NEUMANN, nullptr, dl, s_cur, const_cast<float*>(g), s, alpha, !last};
+      WgradSink step{EPI_WGRAD_NEUMANN, nullptr, dl, s_cur, const_cast<float*>(g), s, alpha, !last || rw};
       step.second_set = pipe;
       hvp_cached(h, os, s_cur, step, pipe);
-      if (pipe && !last) { std::swap(os.Vn, os.Vn2); std::swap(os.Vt, os.Vt2); }
+      if (pipe && step.copies) { std::swap(os.Vn, os.Vn2); std::swap(os.Vt, os.Vt2); }
     }
     s_cur = s;
   }
   if (l2) {
     if (K == 0) launch_mixed_l2(h->ctx, lambda, w, s_cur, alpha, out, h->d);
   } else if (rw) {
-    mixed_reweight_seq(h, os, lambda, s_cur, alpha, out);
+    mixed_reweight_seq(h, os, lambda, s_cur, alpha, out, true);
   } else {
     launch_mixed_prox(h->ctx, h->f(h->logrho), s_cur, alpha, out, h->d);
   }
