@@ -269,7 +269,7 @@ Epilogue blank_epilogue(int mode, int act = 0) {
 // operand copies of a flat parameter-shaped vector: per layer, as stored (n_in x n_out) and
 // transposed; all layers in one launch (eight per launch)
 void make_shadows(betty_handle h, OperandSet& os, const float* flat, float scale,
-                  std::vector<size_t>* N, std::vector<size_t>* T) {
+                  std::vector<size_t>* N, std::vector<size_t>* T, std::vector<size_t>* T32 = nullptr) {
   for (int i0 = 0; i0 < h->L; i0 += MAX_PROBLEMS) {
     ConvertBatch b;
     b.n = std::min(MAX_PROBLEMS, h->L - i0);
@@ -278,6 +278,7 @@ void make_shadows(betty_handle h, OperandSet& os, const float* flat, float scale
       b.j[k] = ConvertJob{flat + li.w_off, li.n_out, scale, li.n_in, li.n_out,
                           N ? h->at<void>((*N)[i0 + k]) : nullptr, li.n_out_p,
                           T ? h->at<void>((*T)[i0 + k]) : nullptr, li.n_in_p};
+      if (T32) b.j[k].outT32 = h->f((*T32)[i0 + k]);
     }
     launch_convert_batch(h->ctx, os.elem, b);
   }
@@ -293,8 +294,8 @@ bool hybrid_forward(betty_handle h, const OperandSet& os) {
 
 // operand copies of the parameters w for everything that follows
 void make_weight_operands(betty_handle h, OperandSet& os, const float* w) {
-  make_shadows(h, os, w, 1.f, &os.Wn, &os.Wt);
-  if (hybrid_forward(h, os)) make_shadows(h, h->sets[1], w, 1.f, nullptr, &h->sets[1].Wt);
+  // (with the fp32 forward of ReLU networks the same launch also leaves the fp32 transposed copies)
+  make_shadows(h, os, w, 1.f, &os.Wn, &os.Wt, hybrid_forward(h, os) ? &h->sets[1].Wt : nullptr);
 }
 
 // Which batches a pass covers: the train (lower) side, the validation (upper) side, or both in

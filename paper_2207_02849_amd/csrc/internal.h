@@ -153,6 +153,7 @@ void launch_gemm_batch(Ctx& ctx, Elem elem, int cfg, GemmBatch& batch, double al
 struct ConvertJob {
   const float* src; long long lds; float scale; int rows, cols;
   void* out; int ld; void* outT; int ldT;
+  float* outT32 = nullptr;    // optional further transposed copy in fp32 (same ldT)
 };
 struct ConvertBatch {
   int n = 0;

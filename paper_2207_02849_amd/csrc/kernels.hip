@@ -75,7 +75,10 @@ __global__ __launch_bounds__(256) void convert_batch_kernel(ConvertBatch b) {
 #pragma unroll 4
   for (int i = 0; i < 16; ++i) {
     const int c = c0 + ty + 4 * i, r = r0 + tx;
-    if (r < j.rows && c < j.cols) outT[(long long)c * j.ldT + r] = from_float<T>(tile[tx][ty + 4 * i]);
+    if (r < j.rows && c < j.cols) {
+      outT[(long long)c * j.ldT + r] = from_float<T>(tile[tx][ty + 4 * i]);
+      if (j.outT32) j.outT32[(long long)c * j.ldT + r] = tile[tx][ty + 4 * i];
+    }
   }
 }
 
