@@ -690,9 +690,22 @@ void mixed_reweight_seq(betty_handle h, OperandSet& os, const float* lam, const 
   const LayerInfo& lo = h->layers[L - 1];
   // c_i is linear in the direction, so the scale is applied once, to the final sum over samples
   if (!copies_current) make_shadows(h, os, qflat, 1.f, nullptr, &os.Vt);   // else os.Vt already holds qflat
-  r_forward(h, os, qflat);
-  launch_loss_directional_rows(h->ctx, h->desc.loss, h->f(sb.P), h->f(sb.ZL), h->batch[0].y,
-                               h->batch[0].target, h->f(os.Rz[L]), lo.n_out_p, sb.B, lo.n_out, h->f(os.cvec));
+  if (L >= 2 && lo.n_out <= LAST_ROP_MAX_C) {
+    // narrow output layer: the last product and the directional derivative in one vector kernel
+    r_forward(h, os, qflat, false, L - 1);
+    LastRopArgs a{};
+    a.RA = h->at<void>(os.RA[L - 1]); a.A = h->at<void>(sb.A[L - 1]); a.lda = lo.n_in_p;
+    a.Wt = h->at<void>(os.Wt[L - 1]); a.Vt = h->at<void>(os.Vt[L - 1]); a.ldt = lo.n_in_p;
+    a.cbias = h->desc.has_bias ? qflat + lo.b_off : nullptr;
+    a.P = h->f(sb.P); a.ldp = lo.n_out_p;
+    a.B = sb.B; a.n_in = lo.n_in; a.n_in_p = lo.n_in_p; a.C = lo.n_out; a.loss = h->desc.loss;
+    a.cvec = h->f(os.cvec); a.y = h->batch[0].y; a.Z = h->f(sb.ZL); a.target = h->batch[0].target;
+    launch_last_layer_rop(h->ctx, os.elem, a);
+  } else {
+    r_forward(h, os, qflat);
+    launch_loss_directional_rows(h->ctx, h->desc.loss, h->f(sb.P), h->f(sb.ZL), h->batch[0].y,
+                                 h->batch[0].target, h->f(os.Rz[L]), lo.n_out_p, sb.B, lo.n_out, h->f(os.cvec));
+  }
   launch_wnet_theta_vjp(h->ctx, h->f(sb.ell), h->f(sb.omega), h->f(os.cvec), lam, h->desc.wnet_hidden, sb.B,
                         scale / (float)sb.B, out);
 }

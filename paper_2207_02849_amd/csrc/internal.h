@@ -195,6 +195,10 @@ struct LastRopArgs {
   void* RDL; void* RDLt; int ldRDLt;                    // out: R delta_L [B][ldd] and [n_out_p][ldRDLt]
   void* RD; int ldRD; void* RDt; int ldRDt;             // out: R delta_{L-1} [B][ldRD] and [n_in_p][ldRDt]
   int B, n_in, n_in_p, C, loss;
+  // Directional form (cvec non-null): only c_i = <dl_i/dz, Rz_L,i> per sample leaves the kernel
+  // (the per-sample directional derivative of the loss, for the reweighting mixed term);
+  // y / (Z, target) give dl/dz for cross-entropy / squared error.
+  float* cvec; const int32_t* y; const float* Z; const float* target;
 };
 constexpr int LAST_ROP_MAX_C = 16;
 void launch_last_layer_rop(Ctx&, Elem, const LastRopArgs&);

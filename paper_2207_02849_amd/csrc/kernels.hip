@@ -272,7 +272,7 @@ __global__ __launch_bounds__(1024) void last_layer_rop_kernel(LastRopArgs a) {
   // kernel pays one memory round trip instead of three.  (The launcher sizes the column splits so
   // that a wavefront has at most one block of 32 columns.)
   const int jb = j_begin + ks * 32;
-  const bool jb_ok = jb < j_end;
+  const bool jb_ok = jb < j_end && !a.cvec;                 // the directional form has no phase 3
   const int j = jb + lane;
   const bool j_ok = jb_ok && lane < 32 && j < j_end;
   u32x4 w3[CP / (2 * EPC)], v3[CP / (2 * EPC)];
@@ -306,9 +306,11 @@ __global__ __launch_bounds__(1024) void last_layer_rop_kernel(LastRopArgs a) {
     const int s = lane >> 4, c = lane & 15, i = i0 + s;
     if (c < a.C && i < a.B) {
       if (a.loss == BETTY_LOSS_SOFTMAX_CE) p2 = a.P[(long long)i * a.ldp + c];
-      s2 = a.s[i];
       if (a.cbias) cb2 = a.cbias[c];
-      d2 = ((const T*)a.DL)[(long long)i * a.ldd + c];
+      if (!a.cvec) {
+        s2 = a.s[i];
+        d2 = ((const T*)a.DL)[(long long)i * a.ldd + c];
+      }
     }
   }
 
@@ -366,28 +368,43 @@ __global__ __launch_bounds__(1024) void last_layer_rop_kernel(LastRopArgs a) {
     for (int q = 0; q < NW; ++q) rz += part[q][lane];
     const bool ok = c < a.C && i < a.B;
     rz = ok ? rz + cb2 : 0.f;
-    const float si = s2;
-    float val;
-    if (a.loss == BETTY_LOSS_SOFTMAX_CE) {
-      const float p = p2;
-      float dot = p * rz;
+    if (a.cvec) {                                           // directional form: one number per sample
+      float term = 0.f;
+      if (ok) {
+        if (a.loss == BETTY_LOSS_SOFTMAX_CE) {
+          const int yy = min(max(a.y[i], 0), a.C - 1);
+          term = p2 * rz - (c == yy ? rz : 0.f);
+        } else {
+          term = 2.f * (a.Z[(long long)i * a.ldp + c] - a.target[(long long)i * a.C + c]) * rz;
+        }
+      }
 #pragma unroll
-      for (int o = 8; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
-      val = si * (p * rz - p * dot);
+      for (int o = 8; o > 0; o >>= 1) term += __shfl_xor(term, o, 64);
+      if (c == 0 && i < a.B) a.cvec[i] = term;
     } else {
-      val = si * 2.f * rz;
-    }
-    const T vt = from_float<T>(val);
-    if (ok) {
-      rdT[s][c] = vt;
-      dlT[s][c] = d2;
-      if (blockIdx.y == 0) {
-        ((T*)a.RDL)[(long long)i * a.ldd + c] = vt;
-        ((T*)a.RDLt)[(long long)c * a.ldRDLt + i] = vt;
+      const float si = s2;
+      float val;
+      if (a.loss == BETTY_LOSS_SOFTMAX_CE) {
+        const float p = p2;
+        float dot = p * rz;
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+        val = si * (p * rz - p * dot);
+      } else {
+        val = si * 2.f * rz;
+      }
+      const T vt = from_float<T>(val);
+      if (ok) {
+        rdT[s][c] = vt;
+        dlT[s][c] = d2;
+        if (blockIdx.y == 0) {
+          ((T*)a.RDL)[(long long)i * a.ldd + c] = vt;
+          ((T*)a.RDLt)[(long long)c * a.ldRDLt + i] = vt;
+        }
       }
     }
   }
-  __syncthreads();
+  __syncthreads();                                          // (every wavefront reaches this, in both forms)
 
   // ---- phase 3
   if (jb_ok) {
@@ -427,7 +444,7 @@ void launch_last_layer_rop(Ctx& ctx, Elem elem, const LastRopArgs& a) {
   const int blocks = (a.B + 3) / 4;
   // column splits: at most one block of 32 columns per wavefront (16 x 32 per workgroup), and
   // enough workgroups to occupy the chip
-  const int splits = std::max((a.n_in + 511) / 512, std::max(1, std::min(256 / blocks, (a.n_in + 31) / 32)));
+  const int splits = a.cvec ? 1 : std::max((a.n_in + 511) / 512, std::max(1, std::min(256 / blocks, (a.n_in + 31) / 32)));
   const dim3 grid(blocks, splits);
   if (elem == ELEM_BF16) last_layer_rop_kernel<__bf16><<<grid, 1024, 0, ctx.stream>>>(a);
   else last_layer_rop_kernel<float><<<grid, 1024, 0, ctx.stream>>>(a);
