@@ -180,7 +180,9 @@ betty_status betty_best_response_neumann(betty_handle h, const float* w, const f
  *               (REWEIGHT_NET or L2_DECAY); only its train batch is used
  * Both handles must describe the same number of parameters and be bound to the same stream.
  * w, v: d floats; theta, dtheta: betty_num_hyper(h_pretrain) floats; all device pointers.
- * Errors are reported on h_pretrain (betty_last_error). */
+ * Errors are reported on h_pretrain (betty_last_error).  A call repeated with identical arguments
+ * replays one captured graph over both handles; binding or setting batches on either handle
+ * discards it.  Per-launch timing must be off on h_finetune. */
 betty_status betty_hypergrad_chain3(betty_handle h_pretrain, betty_handle h_finetune, const float* w,
                                     const float* theta, const float* v, int K_pretrain,
                                     float alpha_pretrain, int K_finetune, float alpha_finetune,

@@ -2,6 +2,7 @@
 // sequences of the five hot-path calls (paper Sec. 3.2; Neumann and finite-difference
 // approximate implicit differentiation followed by the mixed second-order VJP).
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -74,6 +75,7 @@ struct betty_handle_s {
   char* ws = nullptr;
   size_t ws_need = 0;
   bool bound = false, batches = false;
+  unsigned long long epoch = 0;   // process-wide unique stamp of the last betty_bind / betty_set_batches
   betty_batch batch[2]{};
   OperandSet sets[2];        // [0]: element type of desc.prec; [1]: fp32 set for finite differences when prec is bf16
   size_t vec_g = 0, vec_v = 0, vec_p = 0, vec_Hv = 0, vec_wpm = 0, vec_Gm = 0;
@@ -85,9 +87,11 @@ struct betty_handle_s {
     hipGraphExec_t exec = nullptr;
     const void* w = nullptr; const void* lam = nullptr; const void* u = nullptr; void* out = nullptr;
     int K = -1; float alpha = 0.f, eps = 0.f;
+    int K2 = -1; float alpha2 = 0.f; const void* other = nullptr;   // second level of the three-level chain
+    unsigned long long other_epoch = 0;                             // ... and the state of its handle when recorded
     int seen = 0;
   };
-  GraphSlot graph_neumann, graph_fd, graph_cg, graph_br;
+  GraphSlot graph_neumann, graph_fd, graph_cg, graph_br, graph_chain;
   bool use_graphs = true;
   int tune_target_blocks = 256, tune_tile128_min = 512;   // see plan_chain (measured on 512x4096x8192: 64-tiles beat 128-tiles until the grid is several waves deep)
   int tune_wgrad_cfg = GEMM_64x1;
@@ -751,6 +755,11 @@ static void release_side_stream(betty_handle h) {
   h->side_stream = nullptr;
 }
 
+static unsigned long long next_epoch() {
+  static std::atomic<unsigned long long> counter{0};
+  return ++counter;
+}
+
 static void drop_graph(betty_handle_s::GraphSlot& g) {
   if (g.exec) (void)hipGraphExecDestroy(g.exec);
   if (g.graph) (void)hipGraphDestroy(g.graph);
@@ -759,6 +768,7 @@ static void drop_graph(betty_handle_s::GraphSlot& g) {
 
 static void drop_graphs(betty_handle h) {
   drop_graph(h->graph_neumann); drop_graph(h->graph_fd); drop_graph(h->graph_cg); drop_graph(h->graph_br);
+  drop_graph(h->graph_chain);
 }
 
 // Runs `body` (which only enqueues kernels on the bound stream) directly the first time a given
@@ -766,11 +776,14 @@ static void drop_graphs(betty_handle h) {
 // on.  Any capture failure switches graphs off for the handle and runs the body directly.
 template <typename Body>
 static betty_status run_cached(betty_handle h, betty_handle_s::GraphSlot& g, const void* w, const void* lam,
-                               const void* u, void* out, int K, float alpha, float eps, Body body) {
+                               const void* u, void* out, int K, float alpha, float eps, Body body,
+                               int K2 = -1, float alpha2 = 0.f, const void* other = nullptr,
+                               unsigned long long other_epoch = 0) {
   const bool eligible = h->use_graphs && !h->ctx.profiling && h->ctx.stream != nullptr;
   if (!eligible) { body(); return finish(h); }
   const bool same = g.seen > 0 && g.w == w && g.lam == lam && g.u == u && g.out == out && g.K == K &&
-                    g.alpha == alpha && g.eps == eps;
+                    g.alpha == alpha && g.eps == eps && g.K2 == K2 && g.alpha2 == alpha2 && g.other == other &&
+                    g.other_epoch == other_epoch;
   if (same && g.exec) {
     if (hipGraphLaunch(g.exec, h->ctx.stream) != hipSuccess) return fail(h, BETTY_EDEVICE, "hipGraphLaunch failed");
     return BETTY_OK;
@@ -778,6 +791,7 @@ static betty_status run_cached(betty_handle h, betty_handle_s::GraphSlot& g, con
   if (!same) {
     drop_graph(g);
     g.w = w; g.lam = lam; g.u = u; g.out = out; g.K = K; g.alpha = alpha; g.eps = eps; g.seen = 1;
+    g.K2 = K2; g.alpha2 = alpha2; g.other = other; g.other_epoch = other_epoch;
     body();
     return finish(h);
   }
@@ -951,6 +965,7 @@ betty_status betty_bind(betty_handle h, void* workspace, size_t bytes, void* hip
     if (!ok) { (void)hipGetLastError(); release_side_stream(h); }
   }
   drop_graphs(h);
+  h->epoch = next_epoch();
   h->bound = true;
   h->batches = false;
   launch_fill_zero(h->ctx, h->ws, h->ws_need);
@@ -975,6 +990,7 @@ betty_status betty_set_batches(betty_handle h, betty_batch train, betty_batch va
     else CHECK(check_vec(h, b[s].target, s ? "val.target" : "train.target"));
   }
   drop_graphs(h);
+  h->epoch = next_epoch();
   h->batch[0] = train;
   h->batch[1] = val;
   const LayerInfo& l0 = h->layers[0];
@@ -1086,15 +1102,21 @@ betty_status betty_hypergrad_chain3(betty_handle hp, betty_handle hf, const floa
   if (overlaps(dtheta, hp->n_hyper * 4, v, hp->d * 4)) return fail(hp, BETTY_EINVAL, "dtheta overlaps v");
   // rightmost factor first: u = (dv* / dw) grad_v L_U(v) on the finetuning problem (anchor w),
   // kept in that handle's workspace; then (dw* / dtheta) u on the pretraining problem
-  float* u = hf->f(hf->vec_g);
-  neumann_seq(hf, v, w, nullptr, K_ft, alpha_ft, u);
-  if (hf->ctx.first_error != hipSuccess) {
-    betty_status st = fail(hp, BETTY_EDEVICE, "HIP error on the finetune handle: %s", hipGetErrorString(hf->ctx.first_error));
-    hf->ctx.first_error = hipSuccess;
-    return st;
-  }
-  neumann_seq(hp, w, theta, u, K_pre, alpha_pre, dtheta);
-  return finish(hp);
+  if (hf->ctx.profiling) return fail(hp, BETTY_EINVAL, "switch per-launch timing off on the finetune handle first");
+  auto body = [=]() {
+    float* u = hf->f(hf->vec_g);
+    neumann_seq(hf, v, w, nullptr, K_ft, alpha_ft, u);
+    if (hf->ctx.first_error != hipSuccess) {          // reported through the pretrain handle
+      if (hp->ctx.first_error == hipSuccess) hp->ctx.first_error = hf->ctx.first_error;
+      hf->ctx.first_error = hipSuccess;
+    }
+    neumann_seq(hp, w, theta, u, K_pre, alpha_pre, dtheta);
+  };
+  // repeated identical calls replay one captured graph that spans both handles (same stream); the
+  // finetune handle's workspace and batches are part of what the graph has recorded, so its stamp
+  // is part of the key
+  return run_cached(hp, hp->graph_chain, w, theta, v, dtheta, K_pre, alpha_pre, 0.f, body, K_ft, alpha_ft, hf,
+                    hf->epoch);
 }
 
 betty_status betty_hypergrad_fd(betty_handle h, const float* w, const float* lambda, int K, float alpha,

@@ -359,9 +359,11 @@ def run_chain3(pre_wl, ft_wl, K_pre, a_pre, K_ft, a_ft, tol):
     print(pre_wl.name, f"chain3 {err:.2e} finetune factor {err_u:.2e}", flush=True)
     assert torch.equal(got, got2)
     assert err < tol and err_u < tol, (err, err_u)
-    got3 = bp.betty_hypergrad_chain3(bf, w, theta, v, K_pre, a_pre, K_ft, a_ft)
-    torch.cuda.synchronize()
-    assert torch.equal(got, got3)
+    # the repeated call is captured into one graph over both handles, then replayed
+    for _ in range(3):
+        got3 = bp.betty_hypergrad_chain3(bf, w, theta, v, K_pre, a_pre, K_ft, a_ft)
+        torch.cuda.synchronize()
+        assert torch.equal(got, got3)
     bp.close()
     bf.close()
 
@@ -494,3 +496,26 @@ def test_narrow_output_layer_shapes(cfg, prec):
         pytest.skip("ill-conditioned sum for bf16 operands; covered in fp32")
     wl = wk.tiny(prec=prec, **cfg)
     run_all(wl, fd=wl.act != "relu")
+
+
+def test_chain3_graph_follows_the_finetune_handle():
+    """The cached graph of the chain refers to the finetune handle's workspace and batches: new batches
+    on that handle must not be answered from the old graph."""
+    pre_wl, ft_wl = wk.chain3(seed=3)
+    _, ft2 = wk.chain3(seed=4)
+    bp = binding.from_workload(pre_wl)
+    bf = binding.from_workload(ft_wl, stream=bp.stream)
+    w, theta, v = dev(pre_wl.w), dev(pre_wl.lam), dev(ft_wl.w)
+    out = torch.empty(bp.n_hyper, device="cuda")
+    for _ in range(3):
+        bp.betty_hypergrad_chain3(bf, w, theta, v, 3, 0.05, 2, 0.05, out=out)
+    torch.cuda.synchronize()
+    first = out.clone()
+    bf.set_batches(dev(ft2.X_tr), dev(ft2.X_val), dev(ft2.y_tr, torch.int32), dev(ft2.y_val, torch.int32))
+    bp.betty_hypergrad_chain3(bf, w, theta, v, 3, 0.05, 2, 0.05, out=out)
+    torch.cuda.synchronize()
+    assert not torch.equal(out, first)
+    ft_wl.X_tr, ft_wl.X_val, ft_wl.y_tr, ft_wl.y_val = ft2.X_tr, ft2.X_val, ft2.y_tr, ft2.y_val
+    ref = orc.hypergrad_chain3(oracle_problem(pre_wl), oracle_problem(ft_wl), pre_wl.w, pre_wl.lam, ft_wl.w,
+                               3, 0.05, 2, 0.05)
+    assert rel_l2(host(out), ref) < 1e-4
