@@ -901,6 +901,15 @@ betty_status betty_create(const betty_problem_desc* desc, betty_handle* out) {
   if (desc->prec != BETTY_PREC_FP32 && desc->prec != BETTY_PREC_BF16_FP32ACC) return BETTY_EINVAL;
   if (desc->hp == BETTY_HP_REWEIGHT_NET && (desc->wnet_hidden < 1 || desc->wnet_hidden > 65536)) return BETTY_ESHAPE;
 
+  // the kernels index one matrix (a layer's weights, an activation) with 32-bit offsets
+  {
+    const long long bp = padup(std::max(desc->batch_train, desc->batch_val));
+    for (int i = 0; i < desc->n_layers; ++i) {
+      const long long a = padup(desc->dims[i]), b = padup(desc->dims[i + 1]);
+      if (a * b >= (1LL << 31) || bp * a >= (1LL << 31) || bp * b >= (1LL << 31)) return BETTY_ESHAPE;
+    }
+  }
+
   betty_handle h = new (std::nothrow) betty_handle_s();
   if (!h) return BETTY_EDEVICE;
   h->desc = *desc;

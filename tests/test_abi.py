@@ -73,6 +73,10 @@ def test_create_rejects_bad_descriptions(kw, expect):
 def test_create_rejects_bad_dims_and_nulls():
     _, st, _ = _create([8, 0, 3])
     assert st == binding.ESHAPE
+    _, st, _ = _create([65536, 32768, 3])                 # a 2^31-element layer: beyond 32-bit offsets
+    assert st == binding.ESHAPE
+    _, st, _ = _create([1 << 20, 4, 3], batch_train=4096, batch_val=4)   # activation of 2^32 elements
+    assert st == binding.ESHAPE
     lib = binding.load_library()
     assert lib.betty_create(None, None) == binding.ENULL
 
