@@ -10,7 +10,7 @@
 //
 // Launch = a batch of up to MAX_PROBLEMS independent problems plus optional bias-row jobs,
 // flattened on blockIdx.x.  Skinny problems (few output tiles, long K) are split along K *inside*
-// the workgroup: KG groups of 4 wavefronts each take a contiguous range of k-tiles with their own
+// the workgroup: KG groups (of 4 wavefronts, or of one) each take a contiguous range of k-tiles with their own
 // LDS operand buffers, and the groups' accumulators are summed through LDS in group order, so the
 // result is bit-reproducible and no inter-workgroup synchronisation exists.  (Splitting K across
 // workgroups was measured first: the agent-scope fences it needs write back the L2 of every XCD

@@ -1,7 +1,8 @@
-// Non-GEMM kernels of the hypergradient path: fused epilogues that turn fp32 GEMM output
-// (optionally split-K partials) into the next GEMM's operands in both orientations, the
-// row-wise loss kernels, the weight-net kernels, and the streaming kernels over the flat
-// parameter-shaped vectors (Neumann recurrence, finite-difference steps, mixed VJP).
+// Non-GEMM kernels of the hypergradient path: conversion of flat fp32 parameters into GEMM
+// operands in both orientations, the row-wise loss kernels, the two narrow-output-layer kernels
+// (last layer of the first-order and of the R-op passes when the output has at most 16 columns),
+// the weight-net kernels, and the streaming kernels over the flat parameter-shaped vectors
+// (finite-difference steps, conjugate gradient, mixed VJPs, Adam).
 #include <algorithm>
 
 #include "internal.h"
