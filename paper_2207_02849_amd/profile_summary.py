@@ -6,8 +6,8 @@ from --pmc FETCH_SIZE / WRITE_SIZE runs, calibrated against a plain copy of know
     python -m paper_2207_02849_amd.profile_summary pmc    <fetch.db> <write.db> --copy-mib 1024 \
            --kernel gemm_fused_kernel --launches-per-step 48 --steps 4
 
-`source_hash()` identifies the kernel sources a counter summary belongs to; bench.py quotes the
-traffic figure only while the hash still matches.
+`source_hash()` identifies the kernel sources (comments and spacing aside) a counter summary belongs
+to; bench.py quotes the traffic figure only while the hash still matches.
 """
 from __future__ import annotations
 
@@ -21,11 +21,19 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 KERNEL_SOURCES = ["csrc/gemm.hip", "csrc/kernels.hip", "csrc/api.hip", "csrc/internal.h"]
 
 
+def _code_only(text: str) -> str:
+    """Source text without comments and with runs of white space collapsed: what the compiler sees,
+    near enough (string literals in these sources hold no comment markers)."""
+    text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)
+    text = re.sub(r"//[^\n]*", " ", text)
+    return re.sub(r"\s+", " ", text).strip()
+
+
 def source_hash() -> str:
     h = hashlib.sha256()
     for rel in KERNEL_SOURCES:
-        with open(os.path.join(HERE, rel), "rb") as f:
-            h.update(f.read())
+        with open(os.path.join(HERE, rel), "r") as f:
+            h.update(_code_only(f.read()).encode())
     return h.hexdigest()[:16]
 
 
