@@ -46,8 +46,8 @@ struct SideBuf {
   size_t X = 0, XT = 0;                       // a_0 and its transpose
   std::vector<size_t> A, At, D, Dt;           // a_l (1..L-1), delta_l (1..L), each in both orientations
   std::vector<size_t> dphi, e2;               // fp32 phi'(z_l); phi''(z_l) then (delta W^T) phi''
-  size_t ZL = 0, P = 0, ell = 0, s = 0, omega = 0;
-  size_t ell_bar = 0, omega_bar = 0, ell_p = 0;   // frozen / perturbed per-sample values (finite differences, reweighting)
+  size_t ZL = 0, P = 0, ell = 0, s = 0, omega = 0, dsig = 0;   // dsig: omega (1 - omega)
+  size_t ell_bar = 0, omega_bar = 0, dsig_bar = 0, ell_p = 0;   // frozen / perturbed per-sample values (finite differences, reweighting)
 };
 
 // One complete set of GEMM operands in a given element type.
@@ -159,6 +159,8 @@ void plan_side(betty_handle h, Planner& pl, SideBuf& sb, Elem elem, int B, bool 
   sb.omega = pl.take(Bp * 4);
   sb.ell_bar = pl.take(Bp * 4);
   sb.omega_bar = pl.take(Bp * 4);
+  sb.dsig = pl.take(Bp * 4);
+  sb.dsig_bar = pl.take(Bp * 4);
   sb.ell_p = pl.take(Bp * 4);
 }
 
@@ -361,7 +363,7 @@ void forward_and_loss(betty_handle h, OperandSet& os, int sides, const float* w,
     a.theta = theta;
     a.omega_fixed = side == 0 ? omega_fixed : nullptr;
     a.rows = sb.B; a.inv_batch = 1.0f / (float)sb.B;
-    a.ell = h->f(sb.ell); a.s = h->f(sb.s); a.omega = h->f(sb.omega);
+    a.ell = h->f(sb.ell); a.s = h->f(sb.s); a.omega = h->f(sb.omega); a.dsig = h->f(sb.dsig);
     a.P = h->f(sb.P);
     a.D = h->at<void>(sb.D[L]); a.ldD = lo.n_out_p;
     a.Dt = h->at<void>(sb.Dt[L]); a.ldDt = sb.Bp;
@@ -422,7 +424,7 @@ void forward_backward(betty_handle h, OperandSet& os, int sides, const float* w,
     d.y = h->batch[side].y; d.target = h->batch[side].target;
     d.omega_fixed = side == 0 ? omega_fixed : nullptr;
     d.ZL = h->f(sb.ZL); d.P = h->f(sb.P); d.ldz = lo.n_out_p;
-    d.ell = h->f(sb.ell); d.s = h->f(sb.s); d.omega = h->f(sb.omega);
+    d.ell = h->f(sb.ell); d.s = h->f(sb.s); d.omega = h->f(sb.omega); d.dsig = h->f(sb.dsig);
     d.DL = h->at<void>(sb.D[L]); d.DLt = h->at<void>(sb.Dt[L]); d.ldd = lo.n_out_p; d.ldDLt = sb.Bp;
     d.dphi = h->f(sb.dphi[L - 1]); d.e2 = sb.e2[L - 1] ? h->f(sb.e2[L - 1]) : nullptr; d.ldf = lo.n_in_p;
     d.D = h->at<void>(sb.D[L - 1]); d.ldD = lo.n_in_p; d.Dt = h->at<void>(sb.Dt[L - 1]); d.ldDt = sb.Bp;
@@ -710,7 +712,7 @@ void mixed_reweight_seq(betty_handle h, OperandSet& os, const float* lam, const 
     launch_loss_directional_rows(h->ctx, h->desc.loss, h->f(sb.P), h->f(sb.ZL), h->batch[0].y,
                                  h->batch[0].target, h->f(os.Rz[L]), lo.n_out_p, sb.B, lo.n_out, h->f(os.cvec));
   }
-  launch_wnet_theta_vjp(h->ctx, h->f(sb.ell), h->f(sb.omega), h->f(os.cvec), lam, h->desc.wnet_hidden, sb.B,
+  launch_wnet_theta_vjp(h->ctx, h->f(sb.ell), h->f(sb.dsig), h->f(os.cvec), lam, h->desc.wnet_hidden, sb.B,
                         scale / (float)sb.B, out);
 }
 
@@ -1152,6 +1154,7 @@ betty_status betty_hypergrad_fd(betty_handle h, const float* w, const float* lam
       wgrad_batch(h, os, 1, false, init);
       launch_scale_copy(h->ctx, h->f(sb.ell), 1.f, h->f(sb.ell_bar), sb.B);
       launch_scale_copy(h->ctx, h->f(sb.omega), 1.f, h->f(sb.omega_bar), sb.B);
+      launch_scale_copy(h->ctx, h->f(sb.dsig), 1.f, h->f(sb.dsig_bar), sb.B);
       omega_bar = h->f(sb.omega_bar);
     }
     for (int k = 0; k < K; ++k) {
@@ -1184,7 +1187,7 @@ betty_status betty_hypergrad_fd(betty_handle h, const float* w, const float* lam
       make_weight_operands(h, os, wpm);
       forward_and_loss(h, os, SIDE_TRAIN, wpm, lambda, omega_bar);
       launch_fd_loss_diff(h->ctx, h->f(sb.ell_p), h->f(sb.ell), eps, sb.B, h->f(os.cvec));
-      launch_wnet_theta_vjp(h->ctx, h->f(sb.ell_bar), h->f(sb.omega_bar), h->f(os.cvec), lambda,
+      launch_wnet_theta_vjp(h->ctx, h->f(sb.ell_bar), h->f(sb.dsig_bar), h->f(os.cvec), lambda,
                             h->desc.wnet_hidden, sb.B, 1.0f / (float)sb.B, dlambda);
     }
   };

@@ -173,6 +173,7 @@ struct LossArgs {
   const float* omega_fixed;             // reweight only: use these weights instead of R(l_i; theta)
   int rows; float inv_batch;
   float* ell; float* s; float* omega;   // per-sample outputs
+  float* dsig;                          // omega_i (1 - omega_i), formed without cancellation (weight net evaluated here only)
   float* P;                             // softmax probabilities [rows][ldz] (CE)
   void* D; int ldD; void* Dt; int ldDt;  // s_i * dl_i/dz as GEMM operands, both orientations
 };
@@ -213,6 +214,7 @@ struct LastGradSide {
   const float* omega_fixed;                      // sample weights to use instead of the weight net, or null
   float* ZL; float* P; int ldz;                  // out: logits, softmax probabilities, fp32 [B][ldz]
   float* ell; float* s; float* omega;            // out: per-sample loss, scale, weight
+  float* dsig;                                   // out: omega (1 - omega) without cancellation (weight net evaluated here only)
   void* DL; void* DLt; int ldd, ldDLt;           // out: delta_L [B][ldd] and [n_out_p][ldDLt]
   const float* dphi; float* e2; int ldf;         // layer L-1, fp32 [B][ldf]
   void* D; int ldD; void* Dt; int ldDt;          // out: delta_{L-1} [B][ldD] and [n_in_p][ldDt]
@@ -234,7 +236,7 @@ void launch_loss_directional_rows(Ctx&, int loss, const float* P, const float* Z
                                   const float* target, const float* Rz, long long ld, int rows,
                                   int C, float* c);
 // out = -(1/B) sum_i c_i dR(l_i; theta)/dtheta
-void launch_wnet_theta_vjp(Ctx&, const float* ell, const float* omega, const float* c,
+void launch_wnet_theta_vjp(Ctx&, const float* ell, const float* dsig, const float* c,
                            const float* theta, int hidden, int rows, float inv_batch, float* out);
 
 // ---- kernels.hip : flat parameter-shaped vectors ------------------------------------------

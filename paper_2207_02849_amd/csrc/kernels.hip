@@ -146,6 +146,8 @@ __global__ __launch_bounds__(256) void loss_rows_kernel(LossBatch lb) {
       part += a.theta[2 * H + j] * fmaxf(a.theta[j] * ell + a.theta[H + j], 0.f);
     part = wave_sum(part) + a.theta[3 * H];
     omega = 1.f / (1.f + expf(-part));
+    // sigmoid'(x) = sigmoid(x) sigmoid(-x): no 1 - omega, which loses every digit once omega rounds to 1
+    if (lane == 0 && a.dsig) a.dsig[row] = omega / (1.f + expf(part));
   }
   const float s = omega * a.inv_batch;
   if (lane == 0) { a.ell[row] = ell; a.s[row] = s; a.omega[row] = omega; }
@@ -569,7 +571,9 @@ __global__ __launch_bounds__(1024) void last_layer_grad_kernel(LastGradArgs a) {
       for (int hj = c; hj < H; hj += 16) pw += a.theta[2 * H + hj] * fmaxf(a.theta[hj] * ell + a.theta[H + hj], 0.f);
 #pragma unroll
       for (int o = 8; o > 0; o >>= 1) pw += __shfl_xor(pw, o, 64);
-      omega = 1.f / (1.f + expf(-(pw + a.theta[3 * H])));
+      const float logit = pw + a.theta[3 * H];
+      omega = 1.f / (1.f + expf(-logit));
+      if (blockIdx.y == 0 && iok && c == 0 && sd.dsig) sd.dsig[i] = omega / (1.f + expf(logit));
     }
     const float sc = omega * sd.inv_batch;
     const T dv = from_float<T>(sc * dz);
@@ -638,7 +642,7 @@ void launch_loss_directional_rows(Ctx& ctx, int loss, const float* P, const floa
 }
 
 // one block per hidden unit (and one for the output bias): fixed-order sums over the samples
-__global__ __launch_bounds__(256) void wnet_theta_vjp_kernel(const float* ell, const float* omega,
+__global__ __launch_bounds__(256) void wnet_theta_vjp_kernel(const float* ell, const float* dsig,
                                                              const float* cvec, const float* theta, int H,
                                                              int rows, float inv_batch, float* out) {
   __shared__ float red[4];
@@ -647,7 +651,7 @@ __global__ __launch_bounds__(256) void wnet_theta_vjp_kernel(const float* ell, c
   if (j < H) {
     const float u1 = theta[j], b1 = theta[H + j], u2 = theta[2 * H + j];
     for (int i = threadIdx.x; i < rows; i += 256) {
-      const float om = omega[i], ds = cvec[i] * om * (1.f - om);
+      const float ds = cvec[i] * dsig[i];
       const float pre = u1 * ell[i] + b1;
       const float on = pre > 0.f ? 1.f : 0.f;
       a1 += ds * u2 * on * ell[i];
@@ -659,19 +663,16 @@ __global__ __launch_bounds__(256) void wnet_theta_vjp_kernel(const float* ell, c
       out[j] = -inv_batch * a1; out[H + j] = -inv_batch * a2; out[2 * H + j] = -inv_batch * a3;
     }
   } else {
-    for (int i = threadIdx.x; i < rows; i += 256) {
-      const float om = omega[i];
-      a1 += cvec[i] * om * (1.f - om);
-    }
+    for (int i = threadIdx.x; i < rows; i += 256) a1 += cvec[i] * dsig[i];
     a1 = block_sum(a1, red);
     if (threadIdx.x == 0) out[3 * H] = -inv_batch * a1;
   }
 }
 
-void launch_wnet_theta_vjp(Ctx& ctx, const float* ell, const float* omega, const float* c,
+void launch_wnet_theta_vjp(Ctx& ctx, const float* ell, const float* dsig, const float* c,
                            const float* theta, int hidden, int rows, float inv_batch, float* out) {
   Launch l(ctx, BETTY_K_WNET);
-  wnet_theta_vjp_kernel<<<hidden + 1, 256, 0, ctx.stream>>>(ell, omega, c, theta, hidden, rows, inv_batch, out);
+  wnet_theta_vjp_kernel<<<hidden + 1, 256, 0, ctx.stream>>>(ell, dsig, c, theta, hidden, rows, inv_batch, out);
 }
 
 // ------------------------------------------------------------------------------------------

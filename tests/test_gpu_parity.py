@@ -519,3 +519,25 @@ def test_chain3_graph_follows_the_finetune_handle():
     ref = orc.hypergrad_chain3(oracle_problem(pre_wl), oracle_problem(ft_wl), pre_wl.w, pre_wl.lam, ft_wl.w,
                                3, 0.05, 2, 0.05)
     assert rel_l2(host(out), ref) < 1e-4
+
+
+def test_saturated_sample_weights_keep_their_gradient():
+    """Weight-net outputs that round to 1 in fp32 still have a derivative omega (1 - omega) of full
+    relative accuracy (it is formed as sigmoid(x) sigmoid(-x), not by subtracting omega from 1)."""
+    wl = wk.tiny(kind="reweight", act="gelu", loss="ce", dims=(20, 16, 5), batch=40, hidden=8)
+    H = wl.wnet_hidden
+    wl.lam[2 * H:3 * H] = np.abs(wl.lam[2 * H:3 * H]) * 60.0       # large positive logits
+    wl.lam[3 * H] = 8.0
+    prob = oracle_problem(wl)
+    ell = orc.train_losses(prob, wl.w)
+    omega = orc.weight_net(ell, wl.lam.astype(np.float64), H)
+    assert (omega.astype(np.float32) == 1.0).sum() >= 5 and (1.0 - omega).max() > 1e-12
+    b = binding.from_workload(wl)
+    w, lam = dev(wl.w), dev(wl.lam)
+    q = np.random.default_rng(5).standard_normal(wl.d).astype(np.float32)
+    got = host(b.betty_mixed_vjp(w, lam, dev(q)))
+    ref = orc.mixed_vjp(prob, wl.w, wl.lam, q.astype(np.float64))
+    assert rel_l2(got, ref) < 1e-4
+    got = host(b.betty_hypergrad_neumann(w, lam, 2, 0.05))
+    assert rel_l2(got, orc.hypergrad_neumann(prob, wl.w, wl.lam, 2, 0.05)) < 1e-4
+    b.close()
