@@ -9,7 +9,8 @@
  *     dL_U/dlambda = - (d^2 L_L / dlambda dw) H^{-1} grad_w L_U ,  H = d^2 L_L / dw dw,
  * evaluated right-to-left with matrix-vector products only (Sec. 3.2), by the
  * approximate-implicit-differentiation variants the paper lists there: the Neumann
- * series (AID-NMN) and finite differences (AID-FD).
+ * series (AID-NMN), finite differences (AID-FD) and conjugate gradient (AID-CG); the same
+ * operation on an arbitrary vector, and chained over two lower problems (Eq. 2).
  *
  * Model family: an MLP classifier/regressor with L linear layers
  *     a_0 = X,  z_l = a_{l-1} W_l + b_l,  a_l = phi(z_l) (l < L),  output z_L,
@@ -19,7 +20,9 @@
  *                             one weight-decay hyperparameter per parameter), or
  *     BETTY_HP_REWEIGHT_NET:  mean_i R(l_i; theta) l_i with R a 1-H-1 MLP (ReLU hidden,
  *                             sigmoid output) fed the value of l_i as a constant
- *                             (App. B Listing 3, App. C "Meta-Weight-Network"),
+ *                             (App. B Listing 3, App. C "Meta-Weight-Network"), or
+ *     BETTY_HP_PROXIMAL:      mean_i l_i + sum_j rho_j (w_j - a_j)^2 with the anchor a as the
+ *                             upper variable (finetuning level of Sec. 4.3, App. B Listing 5),
  * and upper cost mean_i l_i on the validation batch (Listing 3, level 2).
  *
  * Conventions common to every call
@@ -141,7 +144,9 @@ betty_status betty_mixed_vjp(betty_handle h, const float* w, const float* lambda
 
 /* Neumann-series hypergradient (AID-NMN):
  *   g = grad_w L_U(w); v = p = g; K times { v <- v - alpha H v; p <- p + v }; q = alpha p;
- *   dlambda = betty_mixed_vjp(q).     K >= 0, alpha finite. */
+ *   dlambda = betty_mixed_vjp(q).     K >= 0, alpha finite.
+ * (The partial sum p is carried in the equivalent nested form p <- g + (I - alpha H) p, so the
+ * result agrees with the term-by-term recurrence up to fp32 rounding order.) */
 betty_status betty_hypergrad_neumann(betty_handle h, const float* w, const float* lambda, int K,
                                      float alpha, float* dlambda);
 
