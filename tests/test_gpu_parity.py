@@ -452,6 +452,31 @@ def test_pipelined_recurrence_is_bit_identical_to_the_serial_one(kind, monkeypat
     b1.close()
 
 
+@pytest.mark.parametrize("kind", ["l2", "reweight", "proximal"])
+def test_two_stream_finite_differences_are_bit_identical_to_the_serial_ones(kind, monkeypatch):
+    """Small models evaluate the lower gradient at w + eps v and at w - eps v side by side on two
+    streams, each with operands of its own: same kernels on the same data as one after the other,
+    so not a bit may change, directly launched or replayed from the captured graph."""
+    wl = wk.tiny(kind=kind, act="gelu", dims=(300, 200, 150, 10), batch=130, prec="bf16", hidden=100)
+    w, lam = dev(wl.w), dev(wl.lam)
+    monkeypatch.setenv("BETTY_TUNE", "fd2=0")
+    b0 = binding.from_workload(wl)
+    ref = b0.betty_hypergrad_fd(w, lam, 3, 0.05, 1e-2).clone()
+    ws0 = b0.workspace.numel()
+    b0.close()
+    monkeypatch.setenv("BETTY_TUNE", "fd2=1")
+    b1 = binding.from_workload(wl)
+    assert b1.workspace.numel() > ws0               # the second evaluation has buffers of its own
+    out = torch.empty(b1.n_hyper, device="cuda")
+    for rep in range(4):                          # direct, capture, two replays
+        out.zero_()
+        b1.betty_hypergrad_fd(w, lam, 3, 0.05, 1e-2, out=out)
+        g = b1.betty_lower_grad(w, lam)           # unrelated direct work in between
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), rep
+    b1.close()
+
+
 def test_stored_tiny_hypergradients():
     """The GPU results against expectations stored on disk (written by tests/golden/make_golden.py
     from the oracle alone)."""
