@@ -49,6 +49,17 @@ template <typename T> __device__ __forceinline__ float to_float(T x) { return (f
 // LDS tile; up to MAX_PROBLEMS matrices per launch
 // ------------------------------------------------------------------------------------------
 
+// four consecutive elements of the operand type as one store
+template <typename T> __device__ __forceinline__ void store_quad(T* p, float a, float b, float c, float d);
+template <> __device__ __forceinline__ void store_quad<float>(float* p, float a, float b, float c, float d) {
+  *(float4*)p = make_float4(a, b, c, d);
+}
+template <> __device__ __forceinline__ void store_quad<__bf16>(__bf16* p, float a, float b, float c, float d) {
+  typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+  bf16x4 v = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
+  *(bf16x4*)p = v;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void convert_batch_kernel(ConvertBatch b) {
   __shared__ float tile[64][65];
@@ -58,9 +69,49 @@ __global__ __launch_bounds__(256) void convert_batch_kernel(ConvertBatch b) {
   bid -= b.block_begin[ji];
   const int tiles_x = (j.cols + 63) / 64;
   const int c0 = (bid % tiles_x) * 64, r0 = (bid / tiles_x) * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   T* out = (T*)j.out;
   T* outT = (T*)j.outT;
+  // Four elements per thread and access when the source rows and all destinations allow aligned
+  // 16-byte loads (every weight matrix whose width is a multiple of four); else one by one.
+  const bool quads = j.cols % 4 == 0 && j.lds % 4 == 0 && j.ld % 4 == 0 && j.ldT % 4 == 0 &&
+                     ((uintptr_t)j.src & 15) == 0 && ((uintptr_t)j.out & 15) == 0 &&
+                     ((uintptr_t)j.outT & 15) == 0 && ((uintptr_t)j.outT32 & 15) == 0;
+  if (quads) {
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int rl = ty + 16 * i, r = r0 + rl, c = c0 + 4 * tx;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (r < j.rows && c < j.cols) {
+        v = *(const float4*)(j.src + (long long)r * j.lds + c);
+        v.x *= j.scale; v.y *= j.scale; v.z *= j.scale; v.w *= j.scale;
+        if (out) store_quad<T>(out + (long long)r * j.ld + c, v.x, v.y, v.z, v.w);
+      }
+      tile[rl][4 * tx] = v.x; tile[rl][4 * tx + 1] = v.y; tile[rl][4 * tx + 2] = v.z; tile[rl][4 * tx + 3] = v.w;
+    }
+    if (!outT) return;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int cl = ty + 16 * i, c = c0 + cl, r = r0 + 4 * tx;
+      if (c >= j.cols || r >= j.rows) continue;
+      const float v0 = tile[4 * tx][cl], v1 = tile[4 * tx + 1][cl], v2 = tile[4 * tx + 2][cl], v3 = tile[4 * tx + 3][cl];
+      T* o = outT + (long long)c * j.ldT + r;
+      float* o32 = j.outT32 ? j.outT32 + (long long)c * j.ldT + r : nullptr;
+      if (r + 3 < j.rows) {
+        store_quad<T>(o, v0, v1, v2, v3);
+        if (o32) store_quad<float>(o32, v0, v1, v2, v3);
+      } else {                                     // last rows of a height that is no multiple of four
+        const float v[4] = {v0, v1, v2, v3};
+        for (int k = 0; k < 4 && r + k < j.rows; ++k) {
+          o[k] = from_float<T>(v[k]);
+          if (o32) o32[k] = v[k];
+        }
+      }
+    }
+    return;
+  }
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
 #pragma unroll 4
   for (int i = 0; i < 16; ++i) {
     const int r = r0 + ty + 4 * i, c = c0 + tx;
