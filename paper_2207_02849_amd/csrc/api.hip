@@ -499,7 +499,7 @@ void wgrad_batch(betty_handle h, OperandSet& os, int side, bool rop, const Wgrad
     b.n = std::min(MAX_PROBLEMS, L - l0 + 1);
     double flops = 0;
     for (int i = 0; i < b.n; ++i) {
-      const int l = l0 + i;
+      const int l = l0 + (b.n - 1 - i);         // deepest layer first
       const LayerInfo& li = h->layers[l - 1];
       GemmProblem& p = b.p[i];
       const void* aT = l == 1 ? h->at<void>(sb.XT) : h->at<void>(sb.At[l - 1]);
