@@ -77,7 +77,7 @@ def main():
                          "to calibrate hardware byte counters against when profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (no collectives or sharding); use --gpus 1",
+        print("bench.py: the library runs on exactly one GPU (no collectives or sharding); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
 
