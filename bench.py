@@ -45,7 +45,7 @@ def pmc_traffic_bytes_per_launch(config, which="gemm_fused_kernel"):
     """HBM-side bytes per launch from a committed counter summary (all GEMM launches, or the
     weight-gradient/Neumann instantiation alone), or None when there is no summary for this
     workload or the kernel sources have changed since it was taken."""
-    from paper_2207_02849_amd import profile_summary
+    import profile_summary
     path = os.path.join(ROOT, "profiles", f"{which}_config{config}_pmc.txt")
     if not os.path.exists(path):
         return None
@@ -238,8 +238,11 @@ def main():
     if not args.no_cpu_baseline:
         from threadpoolctl import threadpool_info
         from oracle import betty_oracle as orc
+        y_tr = wl.y_tr
+        if y_tr is None and wl.y_clean is not None:
+            y_tr = orc.apply_label_noise(wl.y_clean, wl.noise_words, wl.noise_alt, wl.noise_p)[0]
         prob = orc.Problem(dims=wl.dims, act=wl.act, loss=wl.loss, hp=wl.hp, has_bias=wl.has_bias,
-                           X_tr=wl.X_tr, X_val=wl.X_val, y_tr=wl.y_tr, y_val=wl.y_val, t_tr=wl.t_tr,
+                           X_tr=wl.X_tr, X_val=wl.X_val, y_tr=y_tr, y_val=wl.y_val, t_tr=wl.t_tr,
                            t_val=wl.t_val, wnet_hidden=wl.wnet_hidden)
         reps, t_cpu = 0, 0.0
         t0 = time.perf_counter()

@@ -30,8 +30,9 @@
  *  - Parameter-shaped vectors (w, v, q, Hv, grad, and lambda for L2 decay) are flat fp32:
  *    [W_1 (n_0 x n_1, row-major), b_1 (n_1), ..., W_L, b_L]; biases absent if has_bias == 0.
  *    For the weight net lambda = theta = [u1 (H), b1 (H), u2 (H), b2 (1)].
- *  - X is row-major batch x n_0 fp32; labels are int32 in [0, n_L); targets are row-major
- *    batch x n_L fp32.
+ *  - X is row-major batch x n_0 fp32; labels are int32 in [0, n_L) (a label outside that range
+ *    is read as the nearest class, 0 or n_L - 1, in the loss and in every derivative alike);
+ *    targets are row-major batch x n_L fp32.
  *  - The caller owns every buffer, including the workspace.  The compute calls never
  *    allocate or free device memory and never synchronise: work is enqueued on the bound
  *    stream, outputs are valid once the caller has synchronised that stream.
@@ -76,7 +77,12 @@ typedef enum { BETTY_LOSS_MSE = 0, BETTY_LOSS_SOFTMAX_CE = 1 } betty_loss;
 typedef enum { BETTY_HP_L2_DECAY = 0, BETTY_HP_REWEIGHT_NET = 1, BETTY_HP_PROXIMAL = 2 } betty_hp;
 /* Arithmetic of the GEMMs: fp32 operands, or operands rounded to bf16 (round to nearest
  * even) with fp32 accumulation.  Loss math, reductions and all parameter-shaped vectors
- * are fp32 in both.  The finite-difference variant always uses fp32 operands. */
+ * are fp32 in both.  Two exceptions under BETTY_PREC_BF16_FP32ACC, each because a bf16 operand
+ * would destroy the quantity being computed: the finite-difference variant always uses fp32
+ * operands (the perturbation e v is far below a bf16 ulp of w), and for BETTY_ACT_RELU the forward
+ * products z_l = a_{l-1} W_l are formed from fp32 operands so that the sign of z_l, i.e. the ReLU
+ * mask, is decided at fp32 accuracy; every backward and forward-over-reverse product of a ReLU
+ * network still takes bf16 operands. */
 typedef enum { BETTY_PREC_FP32 = 0, BETTY_PREC_BF16_FP32ACC = 1 } betty_prec;
 
 typedef struct {

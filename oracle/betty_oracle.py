@@ -170,7 +170,8 @@ def forward(prob: Problem, w, X):
 def sample_losses(prob: Problem, zL, target):
     """Per-sample loss l_i and its derivative in the logits, dl_i/dz_L (B x C)."""
     if prob.loss == "ce":
-        y = np.asarray(target).astype(np.int64)
+        # a label outside [0, C) is read as the nearest class (the library's stated behaviour)
+        y = np.clip(np.asarray(target).astype(np.int64), 0, zL.shape[1] - 1)
         m = zL.max(axis=1, keepdims=True)
         e = np.exp(zL - m)
         Z = e.sum(axis=1, keepdims=True)

@@ -295,6 +295,13 @@ def from_workload(wl, device="cuda:0", stream=None) -> "Betty":
 
     def up(a, dt):
         return None if a is None else torch.as_tensor(a).to(dt).contiguous().to(dev)
-    b.set_batches(up(wl.X_tr, torch.float32), up(wl.X_val, torch.float32), up(wl.y_tr, torch.int32),
+    y_tr = up(wl.y_tr, torch.int32)
+    if y_tr is None and wl.y_clean is not None:
+        # label noise: the train labels are made on the device from the drawn ingredients
+        import numpy as np
+        words = torch.as_tensor(np.ascontiguousarray(wl.noise_words).view(np.int32)).to(dev)
+        y_tr, _ = b.betty_apply_label_noise(up(wl.y_clean, torch.int32), words, up(wl.noise_alt, torch.int32),
+                                            wl.noise_p, want_mask=False)
+    b.set_batches(up(wl.X_tr, torch.float32), up(wl.X_val, torch.float32), y_tr,
                   up(wl.y_val, torch.int32), up(wl.t_tr, torch.float32), up(wl.t_val, torch.float32))
     return b

@@ -171,9 +171,14 @@ void plan_side(betty_handle h, Planner& pl, SideBuf& sb, Elem elem, int B, bool 
   sb.ell_p = pl.take(Bp * 4);
 }
 
-// first_order_only: just what a gradient of the lower cost on the train batch touches
-void plan_set(betty_handle h, Planner& pl, OperandSet& os, Elem elem, bool second_direction_set,
-              bool first_order_only = false) {
+// How much of an operand set exists:
+//  SET_FULL          everything (first-order passes on both batches and the forward-over-reverse passes)
+//  SET_FIRST_ORDER   what first-order gradients on both batches touch (the fp32 set that serves the
+//                    finite-difference variant and the fp32 forward of ReLU networks beside bf16 operands)
+//  SET_TRAIN_ONLY    just what a gradient of the lower cost on the train batch touches
+enum SetScope { SET_FULL, SET_FIRST_ORDER, SET_TRAIN_ONLY };
+
+void plan_set(betty_handle h, Planner& pl, OperandSet& os, Elem elem, bool second_direction_set, SetScope scope) {
   const int L = h->L;
   const size_t es = elem_size(elem);
   os.elem = elem;
@@ -183,10 +188,13 @@ void plan_set(betty_handle h, Planner& pl, OperandSet& os, Elem elem, bool secon
   for (int i = 0; i < L; ++i) {
     const size_t m = (size_t)h->layers[i].n_in_p * h->layers[i].n_out_p * es;
     os.Wn[i] = pl.take(m); os.Wt[i] = pl.take(m);
-    if (!first_order_only) { os.Vn[i] = pl.take(m); os.Vt[i] = pl.take(m); }
+    if (scope == SET_FULL) { os.Vn[i] = pl.take(m); os.Vt[i] = pl.take(m); }
   }
-  if (first_order_only) return;
+  if (scope == SET_TRAIN_ONLY) return;
   plan_side(h, pl, os.side[1], elem, h->desc.batch_val, false);
+  const size_t Bp = os.side[0].Bp;
+  os.cvec = pl.take(Bp * 4);
+  if (scope == SET_FIRST_ORDER) return;
   if (second_direction_set) {
     os.Vn2.assign(L, 0); os.Vt2.assign(L, 0);
     for (int i = 0; i < L; ++i) {
@@ -194,7 +202,6 @@ void plan_set(betty_handle h, Planner& pl, OperandSet& os, Elem elem, bool secon
       os.Vn2[i] = pl.take(m); os.Vt2[i] = pl.take(m);
     }
   }
-  const size_t Bp = os.side[0].Bp;
   os.RA.assign(L + 1, 0); os.RAt.assign(L + 1, 0); os.RD.assign(L + 1, 0); os.RDt.assign(L + 1, 0);
   os.Rz.assign(L + 1, 0);
   for (int l = 1; l <= L; ++l) {
@@ -204,19 +211,18 @@ void plan_set(betty_handle h, Planner& pl, OperandSet& os, Elem elem, bool secon
     os.RDt[l] = pl.take(np * Bp * es);
     os.Rz[l] = pl.take(Bp * np * 4);
   }
-  os.cvec = pl.take(Bp * 4);
 }
 
 void plan(betty_handle h) {
   Planner pl;
   const Elem main_elem = h->desc.prec == BETTY_PREC_BF16_FP32ACC ? ELEM_BF16 : ELEM_F32;
-  plan_set(h, pl, h->sets[0], main_elem, true);
-  if (main_elem == ELEM_BF16) plan_set(h, pl, h->sets[1], ELEM_F32, false);
+  plan_set(h, pl, h->sets[0], main_elem, true, SET_FULL);
+  if (main_elem == ELEM_BF16) plan_set(h, pl, h->sets[1], ELEM_F32, false, SET_FIRST_ORDER);
   const size_t vb = h->d * 4;
   h->vec_g = pl.take(vb); h->vec_v = pl.take(vb); h->vec_p = pl.take(vb); h->vec_Hv = pl.take(vb);
   h->vec_wpm = pl.take(vb); h->vec_Gm = pl.take(vb);
   if (h->fd_two_streams) {
-    plan_set(h, pl, h->fd_minus, ELEM_F32, false, true);
+    plan_set(h, pl, h->fd_minus, ELEM_F32, false, SET_TRAIN_ONLY);
     h->vec_wpm2 = pl.take(vb);
     if (h->desc.hp == BETTY_HP_PROXIMAL) h->vec_g2 = pl.take(vb);
   }

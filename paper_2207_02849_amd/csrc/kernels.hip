@@ -178,9 +178,9 @@ __global__ __launch_bounds__(256) void loss_rows_kernel(LossBatch lb) {
     sum = 0.f;
     for (int c = lane; c < a.C; c += 64) sum += expf(z[c] - m);
     sum = wave_sum(sum);
-    y = a.y[row];
-    const int yy = min(max(y, 0), a.C - 1);      // integer gather of the label's logit
-    ell = logf(sum) + m - z[yy];
+    // a label outside [0, C) is clamped into the range, for the gather and the one-hot alike
+    y = min(max(a.y[row], 0), a.C - 1);
+    ell = logf(sum) + m - z[y];                  // integer gather of the label's logit
   } else {
     const float* t = a.target + (long long)row * a.C;
     float acc = 0.f;
@@ -599,9 +599,8 @@ __global__ __launch_bounds__(1024) void last_layer_grad_kernel(LastGradArgs a) {
       float sum = ex;
 #pragma unroll
       for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
-      y = iok ? sd.y[i] : 0;
-      const int yy = min(max(y, 0), a.C - 1);
-      const float zy = __shfl(z, (lane & ~15) + yy, 64);
+      y = min(max(iok ? sd.y[i] : 0, 0), a.C - 1);      // clamped into [0, C), for the gather and the one-hot alike
+      const float zy = __shfl(z, (lane & ~15) + y, 64);
       ell = logf(sum) + m - zy;
       p = ex / sum;
       dz = p - (c == y ? 1.f : 0.f);

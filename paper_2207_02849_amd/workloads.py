@@ -40,14 +40,15 @@ class Workload:
     eps_scale: float
     X_tr: np.ndarray       # (B_tr, n_0) float32
     X_val: np.ndarray      # (B_val, n_0) float32
-    y_tr: Optional[np.ndarray] = None     # int32 labels (ce), after label noise
+    y_tr: Optional[np.ndarray] = None     # int32 labels (ce); None when they are to be derived from the
+                                          # label-noise ingredients below (each consumer applies the rule itself)
     y_val: Optional[np.ndarray] = None
     t_tr: Optional[np.ndarray] = None     # float32 targets (mse), (B, n_L)
     t_val: Optional[np.ndarray] = None
     w: Optional[np.ndarray] = None        # float32 flat [W_1, b_1, ..., W_L, b_L]
     lam: Optional[np.ndarray] = None      # float32: length d (l2) or 3H+1 (reweight)
     wnet_hidden: int = 100
-    # label-noise ingredients (reweighting workloads): y_tr was produced from these
+    # label-noise ingredients (reweighting workloads): the train labels follow from these
     y_clean: Optional[np.ndarray] = None  # int32
     noise_words: Optional[np.ndarray] = None   # uint32, one per train sample
     noise_alt: Optional[np.ndarray] = None     # int32 replacement class per sample
@@ -68,11 +69,6 @@ def n_params(dims, has_bias=True) -> int:
 
 def _rng(seed: int) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(key=int(seed)))
-
-
-def noise_threshold(p: float) -> int:
-    """Integer threshold T with P(word < T) = p for a uniform 32-bit word."""
-    return min(int(math.floor(p * 4294967296.0)), 4294967296)
 
 
 def _mixture(rng, n_classes, n_in, batches, sigma):
@@ -149,21 +145,20 @@ def reweight_mlp(name, seed, dims, act, prec, batch_tr, batch_val, K, alpha,
                  noise_p, n_classes=10, sigma=2.0, hidden=100):
     """Meta-Weight-Net style reweighting with uniform label noise on the train batch.
 
-    The noisy labels are derived from (y_clean, noise_words, noise_alt, noise_p)
-    by the rule `word < T ? alt : clean`; y_tr holds the result so that callers
-    which do not exercise the masking step can use it directly.
+    Only the ingredients are drawn here: clean labels, one 32-bit word and one replacement
+    class per train sample, and the noise probability.  Turning them into the noisy train labels
+    is part of the method (the integer threshold rule), so `y_tr` stays None and every consumer
+    applies its own implementation of the rule.
     """
     rng = _rng(seed)
     (X_tr, y_clean), (X_val, y_val) = _mixture(rng, n_classes, dims[0], (batch_tr, batch_val), sigma)
     words = rng.integers(0, 2 ** 32, size=batch_tr, dtype=np.uint64).astype(np.uint32)
     alt = rng.integers(0, n_classes, size=batch_tr, dtype=np.int64).astype(np.int32)
-    T = noise_threshold(noise_p)
-    y_tr = np.where(words.astype(np.uint64) < T, alt, y_clean).astype(np.int32)
     w = _init_mlp(rng, dims)
     theta = _init_wnet(rng, hidden)
     return Workload(name=name, dims=tuple(dims), act=act, loss="ce", hp="reweight", prec=prec,
                     has_bias=True, K=K, alpha=alpha, eps_scale=0.01,
-                    X_tr=X_tr, X_val=X_val, y_tr=y_tr, y_val=y_val, w=w, lam=theta,
+                    X_tr=X_tr, X_val=X_val, y_tr=None, y_val=y_val, w=w, lam=theta,
                     wnet_hidden=hidden, y_clean=y_clean, noise_words=words, noise_alt=alt,
                     noise_p=noise_p)
 
@@ -226,7 +221,7 @@ def chain3(seed=0, dims=(6, 5, 4), act="gelu", prec="fp32", batch=9, has_bias=Tr
     """The two lower problems of the three-level program of Sec. 4.3 on one MLP architecture.
 
     Returns (pre, ft).  `pre` is a reweighting problem on "source-domain" data (its own mixture,
-    noisy labels); its parameters `pre.w` are the pretraining weights and `pre.lam` the weight-net
+    label-noise ingredients, train labels left to the consumer); its parameters `pre.w` are the pretraining weights and `pre.lam` the weight-net
     parameters theta.  `ft` is the finetuning problem on "target-domain" data (the source class
     means shifted by a random offset), with the proximal cost anchored at the pretraining weights:
     `ft.lam` is `pre.w`, `ft.w` the finetuned parameters v; ft's validation batch carries the
@@ -248,12 +243,11 @@ def chain3(seed=0, dims=(6, 5, 4), act="gelu", prec="fp32", batch=9, has_bias=Tr
     Xt_val, yt_val = draw(means + shift, batch + 3)
     words = rng.integers(0, 2 ** 32, size=batch, dtype=np.uint64).astype(np.uint32)
     alt = rng.integers(0, C, size=batch, dtype=np.int64).astype(np.int32)
-    ys = np.where(words.astype(np.uint64) < noise_threshold(noise_p), alt, ys_clean).astype(np.int32)
     w = _init_mlp(rng, dims, has_bias)
     v = (w + 0.1 * _init_mlp(rng, dims, has_bias)).astype(np.float32)
     theta = _init_wnet(rng, hidden)
     pre = Workload(name=name + "_pretrain", dims=tuple(dims), act=act, loss="ce", hp="reweight", prec=prec,
-                   has_bias=has_bias, K=K, alpha=alpha, eps_scale=0.01, X_tr=Xs, X_val=Xs_val, y_tr=ys,
+                   has_bias=has_bias, K=K, alpha=alpha, eps_scale=0.01, X_tr=Xs, X_val=Xs_val, y_tr=None,
                    y_val=ys_val, w=w, lam=theta, wnet_hidden=hidden, y_clean=ys_clean, noise_words=words,
                    noise_alt=alt, noise_p=noise_p)
     ft = Workload(name=name + "_finetune", dims=tuple(dims), act=act, loss="ce", hp="proximal", prec=prec,

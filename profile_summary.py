@@ -2,8 +2,8 @@
 profiles/: per-kernel durations from a --kernel-trace run, and per-kernel hardware byte counters
 from --pmc FETCH_SIZE / WRITE_SIZE runs, calibrated against a plain copy of known size.
 
-    python -m paper_2207_02849_amd.profile_summary stats  <results.db>
-    python -m paper_2207_02849_amd.profile_summary pmc    <fetch.db> <write.db> --copy-mib 1024 \
+    python profile_summary.py stats  <results.db>
+    python profile_summary.py pmc    <fetch.db> <write.db> --copy-mib 1024 \
            --kernel gemm_fused_kernel --launches-per-step 48 --steps 4
 
 `source_hash()` identifies the kernel sources (comments and spacing aside) a counter summary belongs
@@ -17,7 +17,7 @@ import os
 import re
 import sqlite3
 
-HERE = os.path.dirname(os.path.abspath(__file__))
+HERE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2207_02849_amd")
 KERNEL_SOURCES = ["csrc/gemm.hip", "csrc/kernels.hip", "csrc/api.hip", "csrc/internal.h"]
 
 

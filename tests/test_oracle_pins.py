@@ -15,7 +15,7 @@ import torch
 
 from oracle import betty_oracle as orc
 from paper_2207_02849_amd import workloads as wk
-from tests.util import oracle_problem, rel_l2
+from tests.util import oracle_problem, rel_l2, train_labels
 
 
 # ---------------------------------------------------------------- helpers
@@ -65,7 +65,7 @@ def torch_costs(wl):
         return ((out - torch.tensor(t, dtype=torch.float64)) ** 2).sum(dim=1)
 
     def lower(w, lam):
-        loss = per_sample(w, Xtr, wl.y_tr, wl.t_tr)
+        loss = per_sample(w, Xtr, train_labels(wl), wl.t_tr)
         if wl.hp == "l2":
             return loss.mean() + (torch.exp(lam) * w * w).sum()
         if wl.hp == "proximal":
@@ -493,8 +493,9 @@ def test_label_noise_integer_rule():
 
 def test_workload_labels_follow_the_noise_rule():
     wl = wk.config(3)
+    assert wl.y_tr is None            # the generator draws the ingredients only
     out, mask = orc.apply_label_noise(wl.y_clean, wl.noise_words, wl.noise_alt, wl.noise_p)
-    assert (out == wl.y_tr).all()
+    assert (out == np.where(mask == 1, wl.noise_alt, wl.y_clean)).all()
     assert 0.25 < mask.mean() < 0.55
     assert wl.d == 792586 and wk.config(2).d == 203530
 
@@ -587,6 +588,72 @@ def test_bilevel_steps_lower_the_validation_loss_on_ridge():
         w, mom, lam, am, av = orc.bilevel_step(prob, w, mom, lam, am, av, t, unroll=20, lr_w=0.1, mu=0.5,
                                                K=40, alpha=0.2, lr_lam=0.05)
     assert val_at(lam) < before
+
+
+@pytest.mark.parametrize("cfg", [TINY[0], TINY[4], TINY[7]])
+def test_lower_sgd_step_matches_torch_sgd(cfg):
+    """Momentum convention and weight decay of the lower optimiser (App. C: SGD with momentum and
+    weight decay) against torch.optim.SGD driven by autograd on the forward-only lower cost."""
+    wl = wk.tiny(**cfg)
+    prob = oracle_problem(wl)
+    lower, _ = torch_costs(wl)
+    lam = wl.lam.astype(np.float64)
+    lt = torch.tensor(lam)
+    wt = torch.tensor(wl.w.astype(np.float64), requires_grad=True)
+    lr, mu, wd = 0.07, 0.9, 0.02
+    opt = torch.optim.SGD([wt], lr=lr, momentum=mu, weight_decay=wd)
+    w, mom = wl.w.astype(np.float64), np.zeros(wl.d)
+    for step in range(4):
+        opt.zero_grad()
+        lower(wt, lt).backward()
+        opt.step()
+        w, mom = orc.lower_sgd_step(prob, w, lam, mom, lr, mu, wd)
+        assert rel_l2(w, wt.detach().numpy()) < 1e-13, step
+        buf = opt.state[wt]["momentum_buffer"].numpy()
+        assert rel_l2(mom, buf) < 1e-13, step
+
+
+@pytest.mark.parametrize("cfg", [TINY[0], TINY[4]])
+def test_bilevel_step_matches_torch_optimisers_and_dense_series(cfg):
+    """The whole step (unrolled lower SGD, truncated-series hypergradient at the unrolled w, Adam on
+    lambda) rebuilt from torch.optim.SGD / torch.optim.Adam and the series written with the dense
+    Hessian and mixed partial from torch autograd: every state vector after each of three steps."""
+    wl = wk.tiny(**cfg)
+    prob = oracle_problem(wl)
+    lower, upper = torch_costs(wl)
+    d = wl.d
+    unroll, lr_w, mu, wd, K, alpha, lr_lam = 2, 0.05, 0.8, 0.01, 3, 0.06, 0.02
+    wt = torch.tensor(wl.w.astype(np.float64), requires_grad=True)
+    lt = torch.tensor(wl.lam.astype(np.float64), requires_grad=True)
+    opt_w = torch.optim.SGD([wt], lr=lr_w, momentum=mu, weight_decay=wd)
+    opt_l = torch.optim.Adam([lt], lr=lr_lam)
+    w, lam = wl.w.astype(np.float64), wl.lam.astype(np.float64)
+    mom, am, av = np.zeros(d), np.zeros_like(lam), np.zeros_like(lam)
+    for t in range(1, 4):
+        for _ in range(unroll):
+            opt_w.zero_grad()
+            wt.grad = torch.autograd.grad(lower(wt, lt), wt)[0]
+            opt_w.step()
+        g, = torch.autograd.grad(lower(wt, lt), wt, create_graph=True)
+        Hr, Mr = [], []
+        for j in range(d):
+            hw, hl = torch.autograd.grad(g[j], (wt, lt), retain_graph=True)
+            Hr.append(hw.numpy())
+            Mr.append(hl.numpy())
+        H, M = np.array(Hr), np.array(Mr)
+        gu = torch.autograd.grad(upper(wt), wt)[0].numpy()
+        A = np.eye(d) - alpha * H
+        S, P = np.zeros_like(H), np.eye(d)
+        for _ in range(K + 1):
+            S += P
+            P = P @ A
+        dlam = -M.T @ (alpha * S @ gu)
+        lt.grad = torch.tensor(dlam)
+        opt_l.step()
+        w, mom, lam, am, av = orc.bilevel_step(prob, w, mom, lam, am, av, t, unroll, lr_w, mu, K, alpha, lr_lam, wd)
+        assert rel_l2(w, wt.detach().numpy()) < 1e-12, t
+        assert rel_l2(mom, opt_w.state[wt]["momentum_buffer"].numpy()) < 1e-12, t
+        assert np.linalg.norm(lam - lt.detach().numpy()) < 1e-9 * lr_lam * math.sqrt(lam.size), t
 
 
 # ---------------------------------------------------------------- three-level chain (Sec. 3.1 Eq. 2, Sec. 4.3)
