@@ -33,7 +33,7 @@ def host(t):
     return t.detach().cpu().numpy().astype(np.float64)
 
 
-def run_all(wl, tol=None, fd=True, big_alpha=None, check_losses=True, stationary=False, cg=None):
+def run_all(wl, tol=None, fd=True, big_alpha=None, check_losses=True, stationary=False, cg=None, mixed_dir="random"):
     """Compares every entry point for one workload; returns the error table.
 
     Parameter-shaped results are held to the tolerance tensor by tensor (every W_l and b_l on its own,
@@ -41,7 +41,9 @@ def run_all(wl, tol=None, fd=True, big_alpha=None, check_losses=True, stationary
     alpha = 1 / ||H|| (power iteration in the oracle), where the H term of the series carries full weight.
     The conjugate-gradient variant presumes a positive definite H (Sec. 3.2): at the untrained w of these
     workloads H is indefinite, so it is compared here with fp32 operands only unless cg=True says that
-    the workload is positive definite (see test_cg_bf16_on_positive_definite_problems)."""
+    the workload is positive definite (see test_cg_bf16_on_positive_definite_problems).
+    mixed_dir: the direction betty_mixed_vjp is applied to, a random vector or ("gradient") the oracle's
+    lower gradient, i.e. a vector of the kind the hypergradient applies it to."""
     tol = TOL[wl.prec] if tol is None else tol
     cg = (wl.prec == "fp32") if cg is None else cg
     prob = oracle_problem(wl)
@@ -77,7 +79,8 @@ def run_all(wl, tol=None, fd=True, big_alpha=None, check_losses=True, stationary
         errs["upper_loss"] = abs(host(lossu)[0] - costu_ref) / abs(costu_ref)
 
     cmp("hvp", b.betty_hvp(w, lam, dev(v)), orc.hvp(prob, w64, lam64, v.astype(np.float64)))
-    cmp("mixed_vjp", b.betty_mixed_vjp(w, lam, dev(v)), orc.mixed_vjp(prob, w64, lam64, v.astype(np.float64)))
+    qd = v if mixed_dir == "random" else g_ref.astype(np.float32)
+    cmp("mixed_vjp", b.betty_mixed_vjp(w, lam, dev(qd)), orc.mixed_vjp(prob, w64, lam64, qd.astype(np.float64)))
 
     hg = b.betty_hypergrad_neumann(w, lam, wl.K, wl.alpha)
     cmp("neumann", hg, orc.hypergrad_neumann(prob, w64, lam64, wl.K, wl.alpha))
@@ -411,6 +414,15 @@ def test_bilevel_steps_follow_the_oracle(kind, prec, tol):
             assert np.linalg.norm(host(lam) - lam64) < 2e-3 * np.linalg.norm(lam64 - wl.lam.astype(np.float64)), t
         else:
             lam = dev(lam64)          # keep both sides on the same trajectory
+        # the Adam kernel on its own, fed the oracle's hypergradient and moments (same inputs on both
+        # sides, so the normalised step can be held to fp32 rounding whatever the operand precision)
+        lam_in, m_in, v_in = lam64 + 0.01, 0.3 * dlam64, 0.5 * dlam64 * dlam64 + 1e-12
+        lam_g, m_g, v_g = dev(lam_in), dev(m_in), dev(v_in)
+        b.betty_upper_adam_step(lam_g, dev(dlam64), m_g, v_g, t + 1, lr_lam)
+        lam_r, m_r, v_r = orc.adam_step(lam_in, dlam64.astype(np.float32).astype(np.float64), m_in.astype(np.float32).astype(np.float64),
+                                        v_in.astype(np.float32).astype(np.float64), t + 1, lr_lam)
+        assert np.abs(host(lam_g) - lam_r).max() < 1e-4 * lr_lam + 1e-6 * np.abs(lam_r).max(), t
+        assert rel_l2(host(m_g), m_r) < 1e-6 and rel_l2(host(v_g), v_r) < 1e-6, t
     with pytest.raises(binding.BettyError) as e:
         b.betty_upper_adam_step(lam, dlam, am, av, 0, lr_lam)
     assert e.value.status == binding.EINVAL
@@ -589,19 +601,62 @@ def test_stored_tiny_hypergradients():
     dict(kind="l2", act="relu", loss="mse", dims=(33, 40, 1), batch=3),
     dict(kind="reweight", act="relu", loss="ce", dims=(130, 70, 2), batch=130, hidden=3),
     dict(kind="proximal", act="gelu", loss="mse", dims=(20, 600, 7), batch=6, prox_rho=0.2, prox_skip_last=True),
+    # two output columns again, with a weight net wide enough for its theta-gradient to be well conditioned
+    dict(kind="reweight", act="relu", loss="ce", dims=(130, 70, 2), batch=130, hidden=32),
+    dict(kind="l2", act="gelu", loss="ce", dims=(130, 70, 2), batch=130),
 ])
 @pytest.mark.parametrize("prec", ["fp32", "bf16"])
 def test_narrow_output_layer_shapes(cfg, prec):
     """Corners of the narrow-output kernels: 1, 2, 7 and 16 columns, batches that are not multiples of
     the four samples a workgroup takes, a hidden layer wider than one pass of the column split, both
     losses, with and without biases and sample weights."""
-    if prec == "bf16" and cfg.get("hidden") == 3:
-        # ten weight-net parameters fed by two classes: the theta-gradient along a random direction is a
-        # sum over samples that cancels to a few percent of its terms, so bf16 operand rounding shows up
-        # amplified (7e-2) although every other output of the same problem is at 2e-3; fp32 covers the shape
-        pytest.skip("ill-conditioned sum for bf16 operands; covered in fp32")
     wl = wk.tiny(prec=prec, **cfg)
-    run_all(wl, fd=wl.act != "relu")
+    # Two classes: along a random direction the per-sample derivatives c_i = <grad l_i, q> have random
+    # signs and the theta-gradient sum_i c_i dR/dtheta cancels to a few percent of its terms, which
+    # amplifies the bf16 operand rounding to 7e-2 although every other output of the same problem is at
+    # 2e-3.  With bf16 operands the mixed term of these two-column problems is therefore applied to a
+    # gradient-shaped direction, as the hypergradient applies it; fp32 keeps the random direction.
+    two_class_bf16 = prec == "bf16" and wl.hp == "reweight" and wl.dims[-1] == 2
+    run_all(wl, fd=wl.act != "relu", mixed_dir="gradient" if two_class_bf16 else "random")
+
+
+# Where the tolerances stop holding although nothing is wrong: one representative of each family a
+# randomized sweep of small problems turned up.  They run (the kernels are the ordinary ones) and are
+# expected to miss the limit; the measured error is in the reason.
+OUTSIDE_TOLERANCE = [
+    pytest.param(dict(kind="reweight", act="gelu", loss="ce", dims=(33, 17, 5), batch=2, hidden=17, prec="bf16", seed=0),
+                 "neumann", 2e-2,
+                 marks=pytest.mark.xfail(strict=False, reason="theta-gradient of the weight net on a batch of two samples: "
+                                         "the sum over samples cancels to a few percent of its terms and amplifies the bf16 "
+                                         "operand rounding (measured 7.2e-2; fp32 operands 1e-6)")),
+    pytest.param(dict(kind="reweight", act="none", loss="mse", dims=(2, 100), batch=3, hidden=100, prec="bf16", seed=153),
+                 "neumann", 2e-2,
+                 marks=pytest.mark.xfail(strict=False, reason="squared error over 100 outputs drives the sample weights into "
+                                         "saturation, where the weight net's derivative is a difference of nearly equal numbers "
+                                         "(measured 2.4e-2 with bf16 operands, 7e-6 with fp32)")),
+    pytest.param(dict(kind="reweight", act="gelu", loss="ce", dims=(17, 16), batch=2, hidden=5, prec="fp32", seed=355),
+                 "fd", 1e-4,
+                 marks=pytest.mark.xfail(strict=False, reason="central differences in fp32: the step eps = 0.01/||v|| divides out "
+                                         "what cancellation has already lost (measured 1.2e-3 on this two-sample problem; "
+                                         "the analytic variants agree to 3e-7)")),
+]
+
+
+@pytest.mark.parametrize("cfg,what,limit", OUTSIDE_TOLERANCE)
+def test_families_outside_the_tolerances(cfg, what, limit):
+    wl = wk.tiny(**cfg)
+    prob = oracle_problem(wl)
+    b = binding.from_workload(wl)
+    w, lam = dev(wl.w), dev(wl.lam)
+    w64, lam64 = wl.w.astype(np.float64), wl.lam.astype(np.float64)
+    if what == "neumann":
+        e = rel_l2(host(b.betty_hypergrad_neumann(w, lam, 3, 0.05)), orc.hypergrad_neumann(prob, w64, lam64, 3, 0.05))
+    else:
+        e = rel_l2(host(b.betty_hypergrad_fd(w, lam, 3, 0.05, 0.01)), orc.hypergrad_fd(prob, w64, lam64, 3, 0.05, 0.01))
+    b.close()
+    print(wl.name, what, f"{e:.2e}", flush=True)
+    assert np.isfinite(e) and e < 0.2          # off by rounding amplification, not wrong
+    assert e < limit
 
 
 def test_chain3_graph_follows_the_finetune_handle():
