@@ -144,6 +144,23 @@ betty_status betty_upper_grad(betty_handle h, const float* w, float* grad_w, flo
 betty_status betty_hvp(betty_handle h, const float* w, const float* lambda, const float* v,
                        float* Hv);
 
+/* betty_hvp for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same product on the same kernels, with the
+ * workspace taken from a fixed array of BETTY_STATIC_SCRATCH_BYTES inside the library's device image
+ * (each GPU the library runs on holds one copy of it until the process ends) instead of a bound
+ * caller workspace.  The handle needs neither betty_bind nor betty_set_batches: the train batch and
+ * the stream are arguments (x, and y or target, are device pointers as in betty_set_batches; NULL
+ * stream = the default stream), and a binding the handle already has is left as it was.  The call
+ * allocates and frees nothing on the device, never synchronises, and launches directly (no graph is
+ * recorded).  It returns BETTY_EWORKSPACE, before any device work, when betty_workspace_bytes(h)
+ * exceeds BETTY_STATIC_SCRATCH_BYTES.  Every call on a GPU uses that GPU's one array (it is cleared
+ * at the start of each call): calls that overlap in time on one GPU, from any handles or streams,
+ * race; calls ordered on one stream do not. */
+#define BETTY_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+size_t betty_static_scratch_bytes(void);
+betty_status betty_hvp_static(betty_handle h, betty_batch train, void* hip_stream, const float* w,
+                              const float* lambda, const float* v, float* Hv);
+
 /* out = - grad_lambda < grad_w L_L(w, lambda), q >   (q held constant), length of lambda. */
 betty_status betty_mixed_vjp(betty_handle h, const float* w, const float* lambda,
                              const float* q, float* out);

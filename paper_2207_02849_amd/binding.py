@@ -79,6 +79,10 @@ def load_library():
     lib.betty_upper_grad.argtypes = [vp, f32p, f32p, f32p]
     lib.betty_hvp.argtypes = [vp, f32p, f32p, f32p, f32p]
     lib.betty_mixed_vjp.argtypes = [vp, f32p, f32p, f32p, f32p]
+    lib.betty_hvp_static.argtypes = [vp, Batch, vp, f32p, f32p, f32p, f32p]
+    lib.betty_hvp_static.restype = C.c_int
+    lib.betty_static_scratch_bytes.argtypes = []
+    lib.betty_static_scratch_bytes.restype = C.c_size_t
     lib.betty_hypergrad_neumann.argtypes = [vp, f32p, f32p, C.c_int, C.c_float, f32p]
     lib.betty_hypergrad_fd.argtypes = [vp, f32p, f32p, C.c_int, C.c_float, C.c_float, f32p]
     lib.betty_hypergrad_cg.argtypes = [vp, f32p, f32p, C.c_int, f32p]
@@ -116,7 +120,9 @@ class Betty:
 
     def __init__(self, dims: Sequence[int], act="relu", loss="ce", hp="l2", prec="fp32", has_bias=True,
                  batch_train=1, batch_val=1, wnet_hidden=100, prox_rho=0.0, prox_skip_last=False,
-                 device="cuda:0", stream=None):
+                 device="cuda:0", stream=None, bind=True):
+        """bind=False leaves the handle without a workspace (none is allocated): only the calls that
+        take no bound workspace work on it (betty_hvp_static)."""
         self.lib = load_library()
         self._dims = (C.c_int * len(dims))(*dims)
         desc = ProblemDesc(len(dims) - 1, self._dims, int(has_bias), ACT[act], LOSS[loss], HP[hp], PREC[prec],
@@ -131,6 +137,11 @@ class Betty:
         self.dims, self.loss, self.hp = tuple(dims), loss, hp
         self.batch_train, self.batch_val = batch_train, batch_val
         nbytes = self.lib.betty_workspace_bytes(self.h)
+        self._keep = []
+        if not bind:
+            self.workspace = None
+            self.stream = torch.cuda.current_stream(self.device) if stream is None else stream
+            return
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         # The library captures repeated calls into HIP graphs and overlaps launches on a second stream;
         # neither is possible on the legacy default stream, so without an explicit stream the handle
@@ -200,6 +211,20 @@ class Betty:
         Hv = out if out is not None else self._vec(self.d)
         self._call(self.lib.betty_hvp, _ptr(w, torch.float32, self.d), _ptr(lam, torch.float32, self.n_hyper),
                                        _ptr(v, torch.float32, self.d), _ptr(Hv, torch.float32, self.d))
+        return Hv
+
+    def betty_hvp_static(self, X_tr, w, lam, v, y_tr=None, t_tr=None, out=None):
+        """betty_hvp on the library's fixed scratch array: allocates nothing on the device inside the
+        library (the output tensor is the caller's, or made here before the call)."""
+        n0, nL = self.dims[0], self.dims[-1]
+        Hv = out if out is not None else self._vec(self.d)
+        self._keep = [X_tr, y_tr, t_tr]
+        tr = Batch(_ptr(X_tr, torch.float32, self.batch_train * n0),
+                   _ptr(y_tr, torch.int32, self.batch_train) if y_tr is not None else None,
+                   _ptr(t_tr, torch.float32, self.batch_train * nL) if t_tr is not None else None)
+        self._call(lambda h, *a: self.lib.betty_hvp_static(h, tr, self.stream.cuda_stream, *a),
+                   _ptr(w, torch.float32, self.d), _ptr(lam, torch.float32, self.n_hyper),
+                   _ptr(v, torch.float32, self.d), _ptr(Hv, torch.float32, self.d))
         return Hv
 
     def betty_mixed_vjp(self, w, lam, q, out=None):

@@ -9,6 +9,7 @@
 #include <cstdlib>
 #include <new>
 #include <cstring>
+#include <mutex>
 
 #include "internal.h"
 
@@ -781,6 +782,20 @@ static void release_side_stream(betty_handle h) {
   h->side_stream = nullptr;
 }
 
+// What a workspace must hold before its first use: zero padding everywhere (fill kernels, no
+// memset nodes), and for the proximal cost log(rho_j) per parameter.
+static void init_workspace(betty_handle h) {
+  launch_fill_zero(h->ctx, h->ws, h->ws_need);
+  if (h->desc.hp == BETTY_HP_PROXIMAL) {
+    // exp(-200) is exactly 0 in fp32, so parameters outside the proximal term get no curvature
+    const LayerInfo& last = h->layers[h->L - 1];
+    const size_t cut = h->desc.prox_skip_last ? last.w_off : h->d;
+    const float lr = h->desc.prox_rho > 0.f ? std::log(h->desc.prox_rho) : -200.f;
+    launch_fill_value(h->ctx, h->f(h->logrho), std::max(lr, -200.f), cut);
+    if (cut < h->d) launch_fill_value(h->ctx, h->f(h->logrho) + cut, -200.f, h->d - cut);
+  }
+}
+
 static unsigned long long next_epoch() {
   static std::atomic<unsigned long long> counter{0};
   return ++counter;
@@ -1005,15 +1020,7 @@ betty_status betty_bind(betty_handle h, void* workspace, size_t bytes, void* hip
   h->epoch = next_epoch();
   h->bound = true;
   h->batches = false;
-  launch_fill_zero(h->ctx, h->ws, h->ws_need);
-  if (h->desc.hp == BETTY_HP_PROXIMAL) {
-    // exp(-200) is exactly 0 in fp32, so parameters outside the proximal term get no curvature
-    const LayerInfo& last = h->layers[h->L - 1];
-    const size_t cut = h->desc.prox_skip_last ? last.w_off : h->d;
-    const float lr = h->desc.prox_rho > 0.f ? std::log(h->desc.prox_rho) : -200.f;
-    launch_fill_value(h->ctx, h->f(h->logrho), std::max(lr, -200.f), cut);
-    if (cut < h->d) launch_fill_value(h->ctx, h->f(h->logrho) + cut, -200.f, h->d - cut);
-  }
+  init_workspace(h);
   return finish(h);
 }
 
@@ -1074,13 +1081,18 @@ betty_status betty_upper_grad(betty_handle h, const float* w, float* grad_w, flo
   return finish(h);
 }
 
-betty_status betty_hvp(betty_handle h, const float* w, const float* lambda, const float* v, float* Hv) {
-  CHECK(check_ready(h));
+static betty_status check_hvp_args(betty_handle h, const float* w, const float* lambda, const float* v, float* Hv) {
   CHECK(check_vec(h, w, "w")); CHECK(check_vec(h, lambda, "lambda")); CHECK(check_vec(h, v, "v"));
   CHECK(check_vec(h, Hv, "Hv"));
   if (overlaps(Hv, h->d * 4, w, h->d * 4) || overlaps(Hv, h->d * 4, v, h->d * 4) ||
       overlaps(Hv, h->d * 4, lambda, h->n_hyper * 4))
     return fail(h, BETTY_EINVAL, "Hv overlaps an input");
+  return BETTY_OK;
+}
+
+// one stand-alone Hessian-vector product: operand copies of w, the forward/backward cache of the
+// train batch, operand copies of v, the forward-over-reverse passes
+static void hvp_seq(betty_handle h, const float* w, const float* lambda, const float* v, float* Hv) {
   OperandSet& os = h->sets[0];
   make_weight_operands(h, os, w);
   prepare_lower(h, os, w, lambda);
@@ -1088,6 +1100,79 @@ betty_status betty_hvp(betty_handle h, const float* w, const float* lambda, cons
   const float* dl = diag_log(h, lambda);
   WgradSink k{EPI_WGRAD, Hv, dl, dl ? v : nullptr, nullptr, nullptr, 0.f, false};
   hvp_cached(h, os, v, k);
+}
+
+betty_status betty_hvp(betty_handle h, const float* w, const float* lambda, const float* v, float* Hv) {
+  CHECK(check_ready(h));
+  CHECK(check_hvp_args(h, w, lambda, v, Hv));
+  hvp_seq(h, w, lambda, v, Hv);
+  return finish(h);
+}
+
+// ---- the same product for callers that cannot allocate device memory ----------------------
+// The workspace is a fixed array in the library's device image; every GPU the library runs on has
+// its own copy at its own address, looked up once per device.
+static __device__ __align__(256) unsigned char scratch[BETTY_STATIC_SCRATCH_BYTES];
+
+static betty_status static_scratch(betty_handle h, char** out) {
+  constexpr int MAX_DEVICES = 64;
+  static std::mutex mu;
+  static char* base[MAX_DEVICES] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES)
+    return fail(h, BETTY_EDEVICE, "no current HIP device (or its index is beyond %d)", MAX_DEVICES - 1);
+  std::lock_guard<std::mutex> lock(mu);
+  if (!base[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail(h, BETTY_EDEVICE, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    base[dev] = (char*)p;
+  }
+  *out = base[dev];
+  return BETTY_OK;
+}
+
+size_t betty_static_scratch_bytes(void) { return BETTY_STATIC_SCRATCH_BYTES; }
+
+betty_status betty_hvp_static(betty_handle h, betty_batch train, void* hip_stream, const float* w,
+                              const float* lambda, const float* v, float* Hv) {
+  if (!h) return BETTY_ENULL;
+  CHECK(check_hvp_args(h, w, lambda, v, Hv));
+  CHECK(check_vec(h, train.x, "train.x"));
+  if (h->desc.loss == BETTY_LOSS_SOFTMAX_CE) CHECK(check_vec(h, train.y, "train.y"));
+  else CHECK(check_vec(h, train.target, "train.target"));
+  if (h->ws_need > BETTY_STATIC_SCRATCH_BYTES)
+    return fail(h, BETTY_EWORKSPACE, "this problem needs %zu bytes of workspace, the library's fixed scratch array holds %zu: "
+                "use betty_bind with a caller-owned workspace and betty_hvp", h->ws_need, (size_t)BETTY_STATIC_SCRATCH_BYTES);
+  char* base = nullptr;
+  CHECK(static_scratch(h, &base));
+  // run on the scratch array and the given stream, with the handle's own binding set aside
+  char* const ws0 = h->ws;
+  const hipStream_t st0 = h->ctx.stream;
+  const bool prof0 = h->ctx.profiling;
+  const betty_batch b0 = h->batch[0], b1 = h->batch[1];
+  h->ws = base;
+  h->ctx.stream = (hipStream_t)hip_stream;
+  h->ctx.profiling = false;                         // (event creation allocates)
+  h->batch[0] = train;
+  h->batch[1] = train;
+  init_workspace(h);                                // the array keeps the last call's contents
+  OperandSet& os = h->sets[0];
+  const LayerInfo& l0 = h->layers[0];
+  SideBuf& sb = os.side[0];
+  launch_convert_dual(h->ctx, os.elem, train.x, l0.n_in, 1.f, sb.B, l0.n_in, h->at<void>(sb.X), l0.n_in_p,
+                      h->at<void>(sb.XT), sb.Bp);
+  if (hybrid_forward(h, os)) {                      // the fp32 forward of ReLU networks reads its own copy of X
+    SideBuf& fb = h->sets[1].side[0];
+    launch_convert_dual(h->ctx, ELEM_F32, train.x, l0.n_in, 1.f, fb.B, l0.n_in, h->at<void>(fb.X), l0.n_in_p,
+                        h->at<void>(fb.XT), fb.Bp);
+  }
+  hvp_seq(h, w, lambda, v, Hv);
+  h->ws = ws0;
+  h->ctx.stream = st0;
+  h->ctx.profiling = prof0;
+  h->batch[0] = b0;
+  h->batch[1] = b1;
   return finish(h);
 }
 
