@@ -254,7 +254,9 @@ enum {
                                s and two operand-type copies written (20 with a diagonal term)        */
   BETTY_K_GEMM_UPDATE_FINAL = 9,  /* the same for the last step of the L2-decay kind, which writes
                                d(lambda) only (s, g, lambda, w read: 20 bytes per parameter)         */
-  BETTY_K_LAST_LAYER = 10   /* the narrow-output-layer kernels (flops = their products)              */
+  BETTY_K_LAST_LAYER = 10,  /* the narrow-output-layer kernels (flops = their products)              */
+  BETTY_K_GEMM_RFWD = 11,   /* one link of the R-forward chain  Rz_l = [Ra_{l-1} | a_{l-1}] [W_l ; V_l]     */
+  BETTY_K_GEMM_RBWD = 12    /* one link of the R-backward chain R delta_{l-1} = [R delta_l | delta_l] [W_l^T ; V_l^T] .* phi' + ... */
 };
 
 /* While enabled, every kernel launch of the handle is bracketed by HIP events on the

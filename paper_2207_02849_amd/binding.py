@@ -24,7 +24,7 @@ PREC = {"fp32": 0, "bf16": 1}
 
 OK, EINVAL, ENULL, ESHAPE, EWORKSPACE, EALIGN, EUNSUPPORTED, EDEVICE = 0, -1, -2, -3, -4, -5, -6, -7
 KIND_NAMES = ["gemm", "epilogue", "loss", "shadow", "vector", "reduce", "wnet", "other", "gemm_update",
-              "gemm_update_final", "last_layer"]
+              "gemm_update_final", "last_layer", "gemm_rfwd", "gemm_rbwd"]
 
 
 class ProblemDesc(C.Structure):

@@ -663,7 +663,9 @@ void launch_gemm_batch(Ctx& ctx, Elem elem, int cfg, GemmBatch& b, double flops,
   if (total <= 0) return;
   const int mode0 = b.p[0].e.mode;
   const int kind = mode0 == EPI_WGRAD_NEUMANN ? BETTY_K_GEMM_UPDATE
-                 : mode0 == EPI_WGRAD_NEUMANN_L2 ? BETTY_K_GEMM_UPDATE_FINAL : BETTY_K_GEMM;
+                 : mode0 == EPI_WGRAD_NEUMANN_L2 ? BETTY_K_GEMM_UPDATE_FINAL
+                 : (mode0 == EPI_RFWD || mode0 == EPI_RFWD_LAST || mode0 == EPI_RFWD_LAST_HESS) ? BETTY_K_GEMM_RFWD
+                 : mode0 == EPI_RBWD ? BETTY_K_GEMM_RBWD : BETTY_K_GEMM;
   Launch l(ctx, kind, flops, bytes);
   hipError_t err = hipSuccess;
   if (elem == ELEM_BF16) launch_elem<__bf16>(cfg, b.p[0].e.mode, total, ctx.stream, b, err);
