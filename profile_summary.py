@@ -5,6 +5,7 @@ from --pmc FETCH_SIZE / WRITE_SIZE runs, calibrated against a plain copy of know
     python profile_summary.py stats  <results.db>
     python profile_summary.py pmc    <fetch.db> <write.db> --copy-mib 1024 \
            --kernel gemm_fused_kernel --launches-per-step 48 --steps 4
+    python profile_summary.py counters <run1.db> <run2.db> ...      (one counter per run, any counters)
 
 `source_hash()` identifies the kernel sources (comments and spacing aside) a counter summary belongs
 to; bench.py quotes the traffic figure only while the hash still matches.
@@ -115,6 +116,30 @@ def print_pmc(fetch_db, write_db, copy_mib, kernel_filter, launches_per_step, st
         print(f"write_bytes_per_launch: {tot_w / tot_calls:.0f}")
 
 
+def print_counters(dbs, kernel_filter):
+    """One table over several single-counter runs of the same command: per kernel, the launches and
+    every counter's value per launch (the sum over the launches divided by their number, so a
+    percentage such as MfmaUtil comes out as its mean over the launches)."""
+    per = {}
+    names = []
+    for db in dbs:
+        for kern, (counter, calls, val) in pmc_totals(db).items():
+            per.setdefault(kern, {})[counter] = (calls, val)
+            if counter not in names:
+                names.append(counter)
+    print(f"source_hash: {source_hash()}")
+    print(f"{'kernel':96s} {'calls':>6s} " + " ".join(f"{n[:24]:>24s}" for n in names))
+    for kern in sorted(per, key=lambda k: -max(c for c, _ in per[k].values())):
+        if kernel_filter and kernel_filter not in kern:
+            continue
+        calls = max(c for c, _ in per[kern].values())
+        cells = []
+        for n in names:
+            c, v = per[kern].get(n, (0, 0.0))
+            cells.append(f"{v / c:24.4g}" if c else f"{'-':>24s}")
+        print(f"{kern[:96]:96s} {calls:6d} " + " ".join(cells))
+
+
 def main():
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -127,9 +152,14 @@ def main():
     p.add_argument("--kernel", default="gemm_fused_kernel")
     p.add_argument("--launches-per-step", type=int, default=0)
     p.add_argument("--steps", type=int, default=0)
+    c = sub.add_parser("counters")
+    c.add_argument("dbs", nargs="+")
+    c.add_argument("--kernel", default="")
     a = ap.parse_args()
     if a.cmd == "stats":
         print_stats(a.db)
+    elif a.cmd == "counters":
+        print_counters(a.dbs, a.kernel)
     else:
         print_pmc(a.fetch_db, a.write_db, a.copy_mib, a.kernel, a.launches_per_step, a.steps)
 
