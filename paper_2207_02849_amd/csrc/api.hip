@@ -98,6 +98,7 @@ struct betty_handle_s {
   bool use_graphs = true;
   int tune_target_blocks = 256, tune_tile128_min = 512;   // see plan_chain (measured on 512x4096x8192: 64-tiles beat 128-tiles until the grid is several waves deep)
   int tune_wgrad_cfg = GEMM_64x1;
+  int tune_wgrad128_min = 512;                // 128-tiles a bf16 weight-gradient launch needs to use the 128-tile kernel (0 = never)
   // For large models the Neumann recurrence overlaps each layer's weight-gradient launch
   // (bandwidth-bound) with the rest of the R-backward chain on a second stream of the same
   // priority.  Every cross-stream dependency costs several microseconds (measured: 5 per product,
@@ -504,6 +505,11 @@ void wgrad_batch(betty_handle h, OperandSet& os, int side, bool rop, const Wgrad
   for (int l0 = l_first; l0 <= L; l0 += MAX_PROBLEMS) {
     GemmBatch b;
     b.n = std::min(MAX_PROBLEMS, L - l0 + 1);
+    // bf16 launches with enough 128-tiles to fill the chip twice take the 128-tile kernel
+    long tiles128 = 0;
+    for (int i = 0; i < b.n; ++i) tiles128 += (long)(h->layers[l0 + i - 1].n_in_p / 128) * (h->layers[l0 + i - 1].n_out_p / 128);
+    const int cfg = (os.elem == ELEM_BF16 && h->tune_wgrad128_min > 0 && tiles128 >= h->tune_wgrad128_min) ? GEMM_128x1
+                                                                                                             : h->tune_wgrad_cfg;
     double flops = 0;
     for (int i = 0; i < b.n; ++i) {
       const int l = l0 + (b.n - 1 - i);         // deepest layer first
@@ -522,7 +528,7 @@ void wgrad_batch(betty_handle h, OperandSet& os, int side, bool rop, const Wgrad
         flops += 4.0 * B * li.n_in * li.n_out;
       }
       p.g.M = li.n_in; p.g.N = li.n_out; p.g.Mp = li.n_in_p; p.g.Np = li.n_out_p;
-      xcd_split(li.n_in_p / gemm_cfg_tile(h->tune_wgrad_cfg), li.n_out_p / gemm_cfg_tile(h->tune_wgrad_cfg), p.g.xgm, p.g.xgn);
+      xcd_split(li.n_in_p / gemm_cfg_tile(cfg), li.n_out_p / gemm_cfg_tile(cfg), p.g.xgm, p.g.xgn);
       Epilogue e = blank_epilogue(k.mode);
       e.ldc = li.n_out;
       e.C = k.C ? k.C + li.w_off : nullptr;
@@ -562,7 +568,7 @@ void wgrad_batch(betty_handle h, OperandSet& os, int side, bool rop, const Wgrad
     else if (k.mode == EPI_WGRAD_INIT) per_param = k.p ? 8.0 : 4.0;
     else if (k.lam) per_param = 12.0;
     if (k.copies) per_param += 4.0;
-    launch_gemm_batch(h->ctx, os.elem, h->tune_wgrad_cfg, b, flops, per_param * params);
+    launch_gemm_batch(h->ctx, os.elem, cfg, b, flops, per_param * params);
   }
 }
 
@@ -970,15 +976,22 @@ betty_status betty_create(const betty_problem_desc* desc, betty_handle* out) {
   }
   h->d = off;
   h->n_hyper = desc->hp == BETTY_HP_REWEIGHT_NET ? (size_t)3 * desc->wnet_hidden + 1 : h->d;
-  h->use_pipeline = h->d >= ((size_t)32 << 20);
-  h->fd_two_streams = !h->use_pipeline;
+  // Large models with fp32 operands overlap each layer's weight-gradient launch with the R-backward
+  // chain (see use_pipeline).  With bf16 operands their weight gradients take the 128-tile kernel,
+  // all layers in one launch behind the chain: measured on the 121M-parameter model, 7.23 ms per
+  // hypergradient against 7.49 ms for the overlapped 64-tile launches and 8.37 ms for overlapped
+  // 128-tile ones (the two streams contend for the same memory path).
+  const bool large = h->d >= ((size_t)32 << 20);
+  h->use_pipeline = large && desc->prec == BETTY_PREC_FP32;
+  h->fd_two_streams = !large;
   h->max_Bp = std::max(padup(desc->batch_train), padup(desc->batch_val));
-  // tuning overrides for experiments: BETTY_TUNE="wgrad=<cfg>,tile128=<n>,blocks=<n>,pipe=<0|1>,fd2=<0|1>" (see plan_chain)
+  // tuning overrides for experiments: BETTY_TUNE="wgrad=<cfg>,wgrad128=<n>,tile128=<n>,blocks=<n>,pipe=<0|1>,fd2=<0|1>" (see plan_chain)
   if (const char* t = getenv("BETTY_TUNE")) {
     int v;
     if (const char* q = strstr(t, "wgrad=")) if (sscanf(q + 6, "%d", &v) == 1 && (v == GEMM_128x1 || v == GEMM_64x1)) h->tune_wgrad_cfg = v;
     if (const char* q = strstr(t, "tile128=")) if (sscanf(q + 8, "%d", &v) == 1 && v > 0) h->tune_tile128_min = v;
     if (const char* q = strstr(t, "blocks=")) if (sscanf(q + 7, "%d", &v) == 1 && v > 0) h->tune_target_blocks = v;
+    if (const char* q = strstr(t, "wgrad128=")) if (sscanf(q + 9, "%d", &v) == 1 && v >= 0) h->tune_wgrad128_min = v;
     if (const char* q = strstr(t, "pipe=")) if (sscanf(q + 5, "%d", &v) == 1) h->use_pipeline = v != 0;
     if (const char* q = strstr(t, "fd2=")) if (sscanf(q + 4, "%d", &v) == 1) h->fd_two_streams = v != 0;
   }

@@ -575,6 +575,342 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
 }
 
 // ------------------------------------------------------------------------------------------
+// weight-gradient launches of large layers (bf16 operands): 128 x 128 tiles, epilogue through LDS
+// ------------------------------------------------------------------------------------------
+//
+// For a layer with millions of parameters the parameter-shaped epilogue (two or more fp32 vectors
+// in, one out, two operand copies out) moves more bytes than the k loop, and with 64-tiles the
+// operand panels cross the L2 -> L1 path twice as often.  This kernel keeps the k loop of
+// gemm_fused_kernel at 128 x 128 but finishes the tile differently: the accumulators go to LDS once,
+// then the tile is worked off in four passes of 32 rows in which a thread owns a 4 x 4 patch, so
+// that every access to the flat fp32 vectors is a 16-byte access and eight neighbouring lanes
+// cover a whole 128-byte line.  The inputs of pass p + 1 are requested before pass p is computed
+// (those of pass 0 before the last two k-tiles are multiplied), and the transposed operand copy
+// leaves through a small LDS staging tile as 16-byte rows.  Two workgroups fit a compute unit, so
+// one streams its epilogue while the other multiplies.
+
+template <int MODE, bool LAM> constexpr int wg_narr() {
+  return MODE == EPI_WGRAD ? (LAM ? 2 : 0) : MODE == EPI_WGRAD_INIT ? 0 : MODE == EPI_WGRAD_NEUMANN ? (LAM ? 3 : 2)
+       : MODE == EPI_WGRAD_SGD ? (LAM ? 4 : 2) : 4;
+}
+template <int MODE, bool LAM> constexpr int wg_nreg() { return wg_narr<MODE, LAM>() > 0 ? wg_narr<MODE, LAM>() : 1; }
+
+constexpr int WG_BT = 128;                 // tile extent
+constexpr int WG_HP = WG_BT + 8;           // pitch of the fp32 accumulator tile in LDS (floats)
+constexpr int WG_PASS = 32;                // rows per epilogue pass
+constexpr int WG_TP = WG_PASS + 8;         // pitch of the transposed staging tile (elements)
+constexpr size_t WG_LDS_OPERANDS = (size_t)2 * 2 * WG_BT * (GEMM_NCH + 1) * 16;
+constexpr size_t WG_LDS_EPILOGUE = (size_t)WG_BT * WG_HP * 4 + (size_t)WG_BT * WG_TP * 2;
+constexpr size_t WG_LDS = WG_LDS_OPERANDS > WG_LDS_EPILOGUE ? WG_LDS_OPERANDS : WG_LDS_EPILOGUE;
+
+// what a workgroup needs of its problem's epilogue, read from the kernel arguments once
+struct WgTile {
+  const float* src[4];                     // fp32 inputs in the order the mode consumes them
+  float* C; float* v; float* p;
+  __bf16* out; __bf16* outT;
+  long long ldc; int ld, ldT;
+  int M, N, m0, n0;
+  float alpha, beta, gamma;
+  bool has_x;
+};
+
+// Rows and columns are clamped into the valid extent instead of being predicated, so the loads of
+// all arrays of a patch are in flight together (a load inside control flow makes the compiler wait
+// for the earlier ones first).  VEC: 16-byte accesses, whole patch inside the column extent.
+template <bool VEC>
+__device__ __forceinline__ void load_patch(const float* __restrict__ p, long long ld, int row0, int col0, int M, int N,
+                                           float (&r)[4][4]) {
+  if constexpr (VEC) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float4 t = *(const float4*)(p + (long long)min(row0 + i, M - 1) * ld + col0);
+      r[i][0] = t.x; r[i][1] = t.y; r[i][2] = t.z; r[i][3] = t.w;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) r[i][j] = p[(long long)min(row0 + i, M - 1) * ld + min(col0 + j, N - 1)];
+  }
+}
+
+template <bool VEC>
+__device__ __forceinline__ void store_patch(float* __restrict__ p, long long ld, int row0, int col0, int M, int N,
+                                            const float (&r)[4][4]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (row0 + i >= M) continue;
+    float* q = p + (long long)(row0 + i) * ld + col0;
+    if constexpr (VEC) {
+      *(float4*)q = make_float4(r[i][0], r[i][1], r[i][2], r[i][3]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (col0 + j < N) q[j] = r[i][j];
+    }
+  }
+}
+
+template <int MODE, bool LAM, bool VEC>
+__device__ __forceinline__ void wg_request(const WgTile& w, int pass, int pr, int pc, float (&in)[wg_nreg<MODE, LAM>()][4][4]) {
+  constexpr int NARR = wg_narr<MODE, LAM>();
+  const int row0 = w.m0 + WG_PASS * pass + 4 * pr, col0 = w.n0 + 4 * pc;
+#pragma unroll
+  for (int k = 0; k < NARR; ++k) load_patch<VEC>(w.src[k], w.ldc, row0, col0, w.M, w.N, in[k]);
+}
+
+// one pass of 32 rows: accumulators from LDS, the mode's update rule, stores.  Every thread of the
+// workgroup calls it (it contains barriers when the transposed copy is asked for).
+template <int MODE, bool LAM, bool VEC>
+__device__ __forceinline__ void wg_finish(const WgTile& w, int pass, int pr, int pc, int tid, const float* hs, __bf16* sT,
+                                          const float (&in)[wg_nreg<MODE, LAM>()][4][4]) {
+  constexpr int NR = wg_nreg<MODE, LAM>();
+  const int row0 = w.m0 + WG_PASS * pass + 4 * pr, col0 = w.n0 + 4 * pc;
+  float acc[4][4], val[4][4], val2[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float4 h4 = *(const float4*)(hs + (WG_PASS * pass + 4 * pr + i) * WG_HP + 4 * pc);
+    acc[i][0] = h4.x; acc[i][1] = h4.y; acc[i][2] = h4.z; acc[i][3] = h4.w;
+  }
+  const float (&I0)[4][4] = in[0];
+  const float (&I1)[4][4] = in[NR > 1 ? 1 : 0];
+  const float (&I2)[4][4] = in[NR > 2 ? 2 : 0];
+  const float (&I3)[4][4] = in[NR > 3 ? 3 : 0];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float a = acc[i][j];
+      if constexpr (MODE == EPI_WGRAD) {                   // I0 = lam, I1 = x
+        val[i][j] = LAM ? a + 2.f * expf(I0[i][j]) * I1[i][j] : a;
+      } else if constexpr (MODE == EPI_WGRAD_INIT) {
+        val[i][j] = a;
+      } else if constexpr (MODE == EPI_WGRAD_NEUMANN) {    // I0 = s, I1 = g, I2 = lam
+        float h = a;
+        if constexpr (LAM) h += 2.f * expf(I2[i][j]) * I0[i][j];
+        val[i][j] = I1[i][j] + (I0[i][j] - w.alpha * h);
+      } else if constexpr (MODE == EPI_WGRAD_NEUMANN_L2) { // I0 = s, I1 = g, I2 = lam, I3 = w
+        const float el = 2.f * expf(I2[i][j]);
+        const float sn = I1[i][j] + (I0[i][j] - w.alpha * (a + el * I0[i][j]));
+        val[i][j] = -el * I3[i][j] * (w.alpha * sn);
+      } else {                                             // SGD: I0 = momentum, I1 = w, I2 = lam, I3 = anchor
+        float gk = a + w.gamma * I1[i][j];
+        if constexpr (LAM) gk += 2.f * expf(I2[i][j]) * (I1[i][j] - (w.has_x ? I3[i][j] : 0.f));
+        const float mk = w.beta * I0[i][j] + gk;
+        val[i][j] = mk;
+        val2[i][j] = I1[i][j] - w.alpha * mk;
+      }
+    }
+  if constexpr (MODE == EPI_WGRAD || MODE == EPI_WGRAD_NEUMANN_L2) {
+    store_patch<VEC>(w.C, w.ldc, row0, col0, w.M, w.N, val);
+    return;
+  } else if constexpr (MODE == EPI_WGRAD_SGD) {
+    store_patch<VEC>(w.v, w.ldc, row0, col0, w.M, w.N, val);
+    store_patch<VEC>(w.p, w.ldc, row0, col0, w.M, w.N, val2);
+    return;
+  } else {
+    if constexpr (MODE == EPI_WGRAD_INIT) {
+      store_patch<VEC>(w.v, w.ldc, row0, col0, w.M, w.N, val);
+      if (w.p) store_patch<VEC>(w.p, w.ldc, row0, col0, w.M, w.N, val);
+    } else {
+      store_patch<VEC>(w.p, w.ldc, row0, col0, w.M, w.N, val);
+    }
+    // operand copies of the new vector: row-major [row][col] and transposed [col][row]; rows beyond
+    // M inside a stored group are padding of the operand and are written as zeros
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (row0 + i >= w.M) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) val[i][j] = 0.f;
+      }
+    if (w.out) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (row0 + i >= w.M) continue;
+        __bf16* o = w.out + (long long)(row0 + i) * w.ld + col0;
+        if constexpr (VEC) {
+          store4<__bf16>(o, val[i]);
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (col0 + j < w.N) o[j] = (__bf16)val[i][j];
+        }
+      }
+    }
+    if (w.outT) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float quad[4] = {val[0][j], val[1][j], val[2][j], val[3][j]};
+        store4<__bf16>(sT + (4 * pc + j) * WG_TP + 4 * pr, quad);
+      }
+      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int q = tid + 256 * u, c = q >> 2, k = q & 3;
+        const int row = w.m0 + WG_PASS * pass + 8 * k;
+        if (w.n0 + c < w.N && row < w.M)
+          *(u32x4*)(w.outT + (long long)(w.n0 + c) * w.ldT + row) = *(const u32x4*)(sT + c * WG_TP + 8 * k);
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// How many passes ahead the epilogue inputs are requested (the ring of register sets below holds
+// one more).  Requesting the whole tile ahead (3, affordable with two input arrays) was measured
+// slower than one pass ahead on the 121M-parameter model: 620 against 576 us per launch.
+template <int MODE, bool LAM> constexpr int wg_depth() { return 1; }
+constexpr int WG_NPASS = WG_BT / WG_PASS;
+
+template <int MODE, bool LAM, bool VEC>
+__device__ __forceinline__ void wg_epilogue(const WgTile& w, int pr, int pc, int tid, const float* hs, __bf16* sT,
+                                            float (&in)[wg_depth<MODE, LAM>() + 1][wg_nreg<MODE, LAM>()][4][4]) {
+  constexpr int DEPTH = wg_depth<MODE, LAM>(), EARLY = DEPTH < 2 ? DEPTH : 2;
+  // (with 16-byte accesses the first EARLY passes were requested inside the k loop)
+#pragma unroll
+  for (int q = VEC ? EARLY : 0; q < DEPTH; ++q) wg_request<MODE, LAM, VEC>(w, q, pr, pc, in[q]);
+#pragma unroll
+  for (int pass = 0; pass < WG_NPASS; ++pass) {
+    if (pass + DEPTH < WG_NPASS) wg_request<MODE, LAM, VEC>(w, pass + DEPTH, pr, pc, in[(pass + DEPTH) % (DEPTH + 1)]);
+    wg_finish<MODE, LAM, VEC>(w, pass, pr, pc, tid, hs, sT, in[pass % (DEPTH + 1)]);
+  }
+}
+
+template <int MODE, bool LAM>
+__global__ __launch_bounds__(256, 2) void wgrad128_kernel(GemmBatch batch) {
+  typedef __bf16 T;
+  constexpr int BT = WG_BT, NCH = GEMM_NCH, ROW = NCH + 1, EPC = 8, KT = NCH * EPC, GT = 256;
+  constexpr int LA = BT * NCH / GT;
+  constexpr int LBUF = 2 * BT * ROW;
+  extern __shared__ u32x4 smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+
+  int bid = blockIdx.x;
+  if (bid >= batch.gemm_blocks) {
+    bid -= batch.gemm_blocks;
+    int j = 0;
+    while (j + 1 < batch.n_bias && bid >= batch.bias_begin[j + 1]) ++j;
+    bias_rows<T, MODE>(batch.bias[j], (bid - batch.bias_begin[j]) * 4 + (threadIdx.x >> 6));
+    return;
+  }
+  int pi = 0;
+  while (pi + 1 < batch.n && bid >= batch.block_begin[pi + 1]) ++pi;
+  const GemmArgs& g = batch.p[pi].g;
+  const Epilogue& e = batch.p[pi].e;
+  const int tile = bid - batch.block_begin[pi];
+  const int tiles_n = g.Np / BT;
+  int tm = tile / tiles_n, tn = tile % tiles_n;
+  if (g.xgm > 0) {                                 // XCD-compact order (see GemmArgs)
+    const int x = tile & 7, q = tile >> 3;
+    const int rm = (g.Mp / BT) / g.xgm, rn = tiles_n / g.xgn;
+    tm = (x / g.xgn) * rm + q / rn;
+    tn = (x % g.xgn) * rn + q % rn;
+  }
+  const int m0 = tm * BT, n0 = tn * BT;
+
+  WgTile w;
+  w.C = e.C; w.v = e.v; w.p = e.p; w.out = (T*)e.out; w.outT = (T*)e.outT;
+  w.ldc = e.ldc; w.ld = e.ld; w.ldT = e.ldT;
+  w.M = g.M; w.N = g.N; w.m0 = m0; w.n0 = n0;
+  w.alpha = e.alpha; w.beta = e.beta; w.gamma = e.gamma;
+  w.has_x = e.x != nullptr;
+  if constexpr (MODE == EPI_WGRAD) { w.src[0] = e.lam; w.src[1] = e.x; w.src[2] = e.lam; w.src[3] = e.lam; }
+  else if constexpr (MODE == EPI_WGRAD_NEUMANN) { w.src[0] = e.x; w.src[1] = e.v; w.src[2] = e.lam; w.src[3] = e.x; }
+  else if constexpr (MODE == EPI_WGRAD_NEUMANN_L2) { w.src[0] = e.p; w.src[1] = e.v; w.src[2] = e.lam; w.src[3] = e.x; }
+  else if constexpr (MODE == EPI_WGRAD_SGD) { w.src[0] = e.v; w.src[1] = e.p; w.src[2] = e.lam; w.src[3] = e.x ? e.x : e.p; }
+  else { w.src[0] = w.src[1] = w.src[2] = w.src[3] = nullptr; }
+  // 16-byte accesses need every flat vector of the tile aligned and the tile inside the columns
+  unsigned long long bits = (unsigned long long)w.C | (unsigned long long)w.v | (unsigned long long)w.p;
+#pragma unroll
+  for (int k = 0; k < wg_narr<MODE, LAM>(); ++k) bits |= (unsigned long long)w.src[k];
+  const bool vec = (bits & 15) == 0 && (w.ldc & 3) == 0 && n0 + BT <= w.N;
+  // patch of this thread inside a pass: eight lanes side by side cover 32 columns of four rows
+  const int pc = 8 * wave + (lane & 7), pr = lane >> 3;
+
+  f32x16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+  const int T0 = g.Kp[0] / KT, TT = T0 + g.Kp[1] / KT;     // an even number of k-tiles (operands are padded to 128)
+  u32x4 ra0[LA], rb0[LA], ra1[LA], rb1[LA];
+  const long long lda0 = g.lda[0], lda1 = g.lda[1], ldb0 = g.ldb[0], ldb1 = g.ldb[1];
+  const T* const Abase0 = (const T*)g.A[0] + (long long)(m0 + tid / NCH) * lda0 + (tid % NCH) * EPC;
+  const T* const Abase1 = (const T*)g.A[1] + (long long)(m0 + tid / NCH) * lda1 + (tid % NCH) * EPC;
+  const T* const Bbase0 = (const T*)g.B[0] + (long long)(n0 + tid / NCH) * ldb0 + (tid % NCH) * EPC;
+  const T* const Bbase1 = (const T*)g.B[1] + (long long)(n0 + tid / NCH) * ldb1 + (tid % NCH) * EPC;
+#define BETTY_WG_GLOAD(RA_, RB_, t_)                                                                 \
+  {                                                                                                  \
+    const bool second_ = (t_) >= T0;                                                                 \
+    const int tt_ = second_ ? (t_) - T0 : (t_);                                                      \
+    const T* Ab_ = (second_ ? Abase1 : Abase0) + (long long)tt_ * KT;                                \
+    const T* Bb_ = (second_ ? Bbase1 : Bbase0) + (long long)tt_ * KT;                                \
+    const long long lda_ = (second_ ? lda1 : lda0) * (GT / NCH);                                    \
+    const long long ldb_ = (second_ ? ldb1 : ldb0) * (GT / NCH);                                    \
+    _Pragma("unroll") for (int i_ = 0; i_ < LA; ++i_) RA_[i_] = *(const u32x4*)(Ab_ + i_ * lda_);    \
+    _Pragma("unroll") for (int i_ = 0; i_ < LA; ++i_) RB_[i_] = *(const u32x4*)(Bb_ + i_ * ldb_);    \
+  }
+  // one k-tile: registers -> LDS buffer buf_, (refill the registers two tiles ahead), multiply.
+  // Two buffers alternate, so a k-tile costs one barrier.
+#define BETTY_WG_STAGE(RA_, RB_, t_, refill_, buf_)                                                  \
+  {                                                                                                  \
+    u32x4* const sA_ = smem + (buf_) * LBUF;                                                         \
+    u32x4* const sB_ = sA_ + BT * ROW;                                                               \
+    _Pragma("unroll") for (int i_ = 0; i_ < LA; ++i_) {                                              \
+      const int idx_ = tid + i_ * GT;                                                                \
+      sA_[(idx_ / NCH) * ROW + idx_ % NCH] = RA_[i_];                                                \
+      sB_[(idx_ / NCH) * ROW + idx_ % NCH] = RB_[i_];                                                \
+    }                                                                                                \
+    __syncthreads();                                                                                 \
+    if (refill_) BETTY_WG_GLOAD(RA_, RB_, (t_) + 2)                                                  \
+    _Pragma("unroll") for (int j_ = 0; j_ < NCH / 2; ++j_) {                                         \
+      const int c_ = 2 * j_ + (lane >> 5);                                                           \
+      u32x4 af_[2], bf_[2];                                                                          \
+      _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_) {                                             \
+        af_[i_] = sA_[(wm * 64 + i_ * 32 + (lane & 31)) * ROW + c_];                                 \
+        bf_[i_] = sB_[(wn * 64 + i_ * 32 + (lane & 31)) * ROW + c_];                                 \
+      }                                                                                              \
+      _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_)                                               \
+        _Pragma("unroll") for (int jn_ = 0; jn_ < 2; ++jn_)                                          \
+          MfmaChunk<T>::run(af_[i_], bf_[jn_], acc[i_ * 2 + jn_]);                                   \
+    }                                                                                                \
+  }
+  BETTY_WG_GLOAD(ra0, rb0, 0)
+  BETTY_WG_GLOAD(ra1, rb1, 1)
+  int it = 0;
+  for (; it + 2 < TT; it += 2) {
+    BETTY_WG_STAGE(ra0, rb0, it, true, 0)
+    BETTY_WG_STAGE(ra1, rb1, it + 1, true, 1)
+  }
+  // every operand load is issued: request the inputs of the first epilogue pass behind them
+  float in[wg_depth<MODE, LAM>() + 1][wg_nreg<MODE, LAM>()][4][4];
+  if (vec) {
+#pragma unroll
+    for (int q = 0; q < (wg_depth<MODE, LAM>() < 2 ? wg_depth<MODE, LAM>() : 2); ++q) wg_request<MODE, LAM, true>(w, q, pr, pc, in[q]);
+  }
+  BETTY_WG_STAGE(ra0, rb0, it, false, 0)
+  BETTY_WG_STAGE(ra1, rb1, it + 1, false, 1)
+#undef BETTY_WG_STAGE
+#undef BETTY_WG_GLOAD
+
+  // accumulators -> LDS (the operand buffers are dead): register r of lane l of block (i, j) is
+  // element [64 wm + 32 i + 8 (r / 4) + 4 (l / 32) + r % 4][64 wn + 32 j + l % 32]
+  __syncthreads();
+  float* const hs = (float*)smem;
+  __bf16* const sT = (__bf16*)(hs + BT * WG_HP);
+#pragma unroll
+  for (int ij = 0; ij < 4; ++ij)
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      hs[(wm * 64 + (ij >> 1) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * WG_HP + wn * 64 + (ij & 1) * 32 + (lane & 31)] = acc[ij][r];
+  __syncthreads();
+  if (vec) wg_epilogue<MODE, LAM, true>(w, pr, pc, tid, hs, sT, in);
+  else wg_epilogue<MODE, LAM, false>(w, pr, pc, tid, hs, sT, in);
+}
+
+// ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
 
@@ -622,10 +958,36 @@ static void launch_wgrad_mode(int mode, int total, hipStream_t st, const GemmBat
 }
 #undef BETTY_CASE
 
+template <int MODE, bool LAM>
+static void launch_wgrad128_one(int total, hipStream_t st, const GemmBatch& b, hipError_t& err) {
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)wgrad128_kernel<MODE, LAM>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)WG_LDS);
+    if (e != hipSuccess) { err = e; return; }
+    configured = true;
+  }
+  wgrad128_kernel<MODE, LAM><<<total, 256, WG_LDS, st>>>(b);
+}
+
+// bf16 weight-gradient launches on 128-tiles; the L2-decay term (lam) is the same for every problem of a batch
+static void launch_wgrad128(int mode, int total, hipStream_t st, const GemmBatch& b, hipError_t& err) {
+  const bool lam = b.p[0].e.lam != nullptr;
+  switch (mode) {
+#define BETTY_CASE_W(M_) case M_: if (lam) launch_wgrad128_one<M_, true>(total, st, b, err); else launch_wgrad128_one<M_, false>(total, st, b, err); break;
+    BETTY_CASE_W(EPI_WGRAD) BETTY_CASE_W(EPI_WGRAD_NEUMANN) BETTY_CASE_W(EPI_WGRAD_SGD)
+#undef BETTY_CASE_W
+    case EPI_WGRAD_INIT: launch_wgrad128_one<EPI_WGRAD_INIT, false>(total, st, b, err); break;
+    case EPI_WGRAD_NEUMANN_L2: launch_wgrad128_one<EPI_WGRAD_NEUMANN_L2, true>(total, st, b, err); break;
+    default: err = hipErrorInvalidValue; break;
+  }
+}
+
 template <typename T>
 static void launch_elem(int cfg, int mode, int total, hipStream_t st, const GemmBatch& b, hipError_t& err) {
   if (mode >= EPI_WGRAD) {
-    if (cfg == GEMM_128x1) launch_wgrad_mode<T, 128>(mode, total, st, b, err);
+    if (cfg == GEMM_128x1 && sizeof(T) == 2) launch_wgrad128(mode, total, st, b, err);
+    else if (cfg == GEMM_128x1) launch_wgrad_mode<T, 128>(mode, total, st, b, err);
     else if (cfg == GEMM_64x1) launch_wgrad_mode<T, 64>(mode, total, st, b, err);
     else err = hipErrorInvalidValue;
     return;

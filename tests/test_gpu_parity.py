@@ -545,6 +545,49 @@ def test_pipelined_recurrence_is_bit_identical_to_the_serial_one(kind, monkeypat
     b1.close()
 
 
+@pytest.mark.parametrize("kind,dims,pipe", [("l2", (300, 200, 150, 10), 0), ("reweight", (300, 200, 150, 10), 1),
+                                            ("proximal", (300, 200, 150, 10), 0), ("l2", (260, 256, 128), 1),
+                                            ("reweight", (129, 131, 7), 0)])
+def test_large_layer_weight_gradient_kernel_agrees_with_the_default_one(kind, dims, pipe, monkeypatch):
+    """bf16 layers with millions of parameters take a weight-gradient kernel of their own (128-tiles,
+    epilogue staged through LDS); forced on here for small ragged models, where it covers tiles that
+    end inside the rows, inside the columns, and unaligned parameter slices.  Same products in the
+    same order as the default kernel, so the two agree to fp32 rounding of the epilogue, on every
+    entry point that ends in a weight-gradient launch; the Neumann result also against the oracle."""
+    wl = wk.tiny(kind=kind, act="gelu", dims=dims, batch=130, prec="bf16", hidden=100)
+    w, lam = dev(wl.w), dev(wl.lam)
+    v = dev(np.random.default_rng(5).standard_normal(wl.w.size).astype(np.float32))
+
+    def everything(b):
+        res = {"grad": b.betty_lower_grad(w, lam).clone(), "hvp": b.betty_hvp(w, lam, v).clone(),
+               "neumann3": b.betty_hypergrad_neumann(w, lam, 3, 0.05).clone(),
+               "neumann4": b.betty_hypergrad_neumann(w, lam, 4, 0.05).clone(),
+               "fd": b.betty_hypergrad_fd(w, lam, 2, 0.05, 1e-2).clone()}
+        w2, mom = w.clone(), 0.1 * v
+        for _ in range(2):
+            b.betty_lower_sgd_step(w2, lam, mom, 0.05, 0.9, 1e-3)
+        res["sgd_w"], res["sgd_mom"] = w2, mom
+        torch.cuda.synchronize()
+        return res
+
+    monkeypatch.setenv("BETTY_TUNE", f"pipe={pipe},wgrad128=0")
+    b0 = binding.from_workload(wl)
+    ref = everything(b0)
+    b0.close()
+    monkeypatch.setenv("BETTY_TUNE", f"pipe={pipe},wgrad128=1")
+    b1 = binding.from_workload(wl)
+    got = everything(b1)
+    again = b1.betty_hypergrad_neumann(w, lam, 3, 0.05)          # replay of the captured graph
+    torch.cuda.synchronize()
+    assert torch.equal(again, got["neumann3"])
+    b1.close()
+    for name in ref:
+        err = rel_l2(host(got[name]), host(ref[name]))
+        print(wl.name, name, f"{err:.2e}", flush=True)
+        assert err < 1e-5, (name, err)
+    assert rel_l2(host(got["neumann4"]), orc.hypergrad_neumann(oracle_problem(wl), wl.w, wl.lam, 4, 0.05)) < 2e-2
+
+
 @pytest.mark.parametrize("kind", ["l2", "reweight", "proximal"])
 def test_two_stream_finite_differences_are_bit_identical_to_the_serial_ones(kind, monkeypatch):
     """Small models evaluate the lower gradient at w + eps v and at w - eps v side by side on two
