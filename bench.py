@@ -347,6 +347,13 @@ def main():
                 "tflops": hvp_flops / t_hvp / 1e12, "frac_of_bf16_mfma_peak": hvp_flops / t_hvp / 1e12 / peak},
         "phases": phases,
         "fd_hypergradients_per_s": (1.0 / t_fd) if t_fd else None,
+        # the finite-difference variant forms its products from fp32 operands (the difference of two
+        # gradients eps apart needs fp32 accuracy), so fp32 MFMA is the roof of its GEMMs: one upper
+        # gradient plus 2K lower gradients, each a forward, a backward and a weight-gradient pass
+        "fd": None if not t_fd else {
+            "ms": t_fd * 1e3, "algorithmic_gflop": (2 * K + 1) * grad_flops / 1e9,
+            "tflops": (2 * K + 1) * grad_flops / t_fd / 1e12,
+            "frac_of_fp32_mfma_peak": (2 * K + 1) * grad_flops / t_fd / 1e12 / PEAK_FP32_MFMA_TFLOPS},
         "bilevel_upper_steps_per_s": {"value": 1.0 / t_bilevel,
                                       "step": "1 lower momentum-SGD step + Neumann hypergradient + Adam step on lambda"},
         "chain3_hypergradients_per_s": None if t_chain is None else {

@@ -98,6 +98,7 @@ struct betty_handle_s {
   bool use_graphs = true;
   int tune_target_blocks = 256, tune_tile128_min = 512;   // see plan_chain (measured on 512x4096x8192: 64-tiles beat 128-tiles until the grid is several waves deep)
   int tune_wgrad_cfg = GEMM_64x1;
+  int tune_rect_max = 1024, tune_rect_min_tt = 16;  // see plan_chain
   int tune_wgrad128_min = 512;                // 128-tiles a bf16 weight-gradient launch needs to use the 128-tile kernel (0 = never)
   // For large models the Neumann recurrence overlaps each layer's weight-gradient launch
   // (bandwidth-bound) with the rest of the R-backward chain on a second stream of the same
@@ -253,7 +254,13 @@ OperandSet& fd_operands(betty_handle h) { return h->sets[1].present ? h->sets[1]
 //  * 128-tiles once there are enough of them to fill the chip several times over;
 //  * 32-tiles with an eight-way K split inside the workgroup when even 64-tiles would leave half
 //    the compute units idle (batch 256 against 1024-wide layers);
-//  * otherwise 64-tiles, K split four ways while the grid is still small.
+//  * 64-tiles with K split four ways while the grid is still small;
+//  * 128 x 64 tiles when 64-tiles would come to between one and four per compute unit and the
+//    reduction is long: such a launch is bound by what a compute unit can pull through its L1
+//    (measured: about 63 GB/s each with all of them pulling), and a 128 x 64 tile fetches 192
+//    operand rows for the 8192 outputs that two 64-tiles fetch 256 for (121M-parameter model,
+//    batch 512: R-forward link 73 -> 66 us, backward link 76 -> 60 us);
+//  * otherwise plain 64-tiles.
 // Measured and dropped: 128-tiles with a two-way K split (2 x 512 x 4096 x 4096: 78 us against
 // 73 us for plain 64-tiles), and 64-tiles computed by one wavefront each over a quarter of K
 // (faster stand-alone, 54 against 62 us on 512 x 4096 x 8192, but 4 % slower with the real
@@ -264,6 +271,7 @@ int plan_chain(betty_handle h, Elem elem, int tiles128, int Ktot_p) {
   const int tiles64 = 4 * tiles128;
   if (tiles64 <= h->tune_target_blocks / 2 && TT >= 16) return GEMM_32x8;
   if (tiles64 < h->tune_target_blocks && TT >= 8) return GEMM_64x4;
+  if (tiles64 <= h->tune_rect_max && TT >= h->tune_rect_min_tt) return GEMM_128x64;
   return GEMM_64x1;
 }
 
@@ -985,12 +993,14 @@ betty_status betty_create(const betty_problem_desc* desc, betty_handle* out) {
   h->use_pipeline = large && desc->prec == BETTY_PREC_FP32;
   h->fd_two_streams = !large;
   h->max_Bp = std::max(padup(desc->batch_train), padup(desc->batch_val));
-  // tuning overrides for experiments: BETTY_TUNE="wgrad=<cfg>,wgrad128=<n>,tile128=<n>,blocks=<n>,pipe=<0|1>,fd2=<0|1>" (see plan_chain)
+  // tuning overrides for experiments: BETTY_TUNE="wgrad=<cfg>,wgrad128=<n>,tile128=<n>,blocks=<n>,rect=<n>,rectk=<n>,pipe=<0|1>,fd2=<0|1>" (see plan_chain)
   if (const char* t = getenv("BETTY_TUNE")) {
     int v;
     if (const char* q = strstr(t, "wgrad=")) if (sscanf(q + 6, "%d", &v) == 1 && (v == GEMM_128x1 || v == GEMM_64x1)) h->tune_wgrad_cfg = v;
     if (const char* q = strstr(t, "tile128=")) if (sscanf(q + 8, "%d", &v) == 1 && v > 0) h->tune_tile128_min = v;
     if (const char* q = strstr(t, "blocks=")) if (sscanf(q + 7, "%d", &v) == 1 && v > 0) h->tune_target_blocks = v;
+    if (const char* q = strstr(t, "rect=")) if (sscanf(q + 5, "%d", &v) == 1 && v >= 0) h->tune_rect_max = v;
+    if (const char* q = strstr(t, "rectk=")) if (sscanf(q + 6, "%d", &v) == 1 && v > 0) h->tune_rect_min_tt = v;
     if (const char* q = strstr(t, "wgrad128=")) if (sscanf(q + 9, "%d", &v) == 1 && v >= 0) h->tune_wgrad128_min = v;
     if (const char* q = strstr(t, "pipe=")) if (sscanf(q + 5, "%d", &v) == 1) h->use_pipeline = v != 0;
     if (const char* q = strstr(t, "fd2=")) if (sscanf(q + 4, "%d", &v) == 1) h->fd_two_streams = v != 0;
@@ -1020,6 +1030,14 @@ betty_status betty_bind(betty_handle h, void* workspace, size_t bytes, void* hip
   if (bytes < h->ws_need) return fail(h, BETTY_EWORKSPACE, "workspace has %zu bytes, %zu needed", bytes, h->ws_need);
   h->ws = (char*)workspace;
   h->ctx.stream = (hipStream_t)hip_stream;
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      h->ctx.num_cus = cus;
+    else
+      (void)hipGetLastError();
+  }
   if (!h->side_stream && hip_stream != nullptr) {
     // second stream (default priority) and the events that order it against the bound stream
     bool ok = hipStreamCreateWithFlags(&h->side_stream, hipStreamNonBlocking) == hipSuccess;

@@ -440,8 +440,11 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
   }
 
   // Two register sets hold the global loads of the next two k-tiles, so two tiles' worth of
-  // loads are in flight while a third is multiplied out of LDS.
+  // loads are in flight while a third is multiplied out of LDS (four sets in the long-loop form
+  // of the unsplit activation-shaped launches, see below).
+  constexpr bool LONG_LOOP = KG == 1 && MODE < EPI_WGRAD;
   u32x4 ra0[LA], rb0[LB], ra1[LA], rb1[LB];
+  u32x4 ra2[LONG_LOOP ? LA : 1], rb2[LONG_LOOP ? LB : 1], ra3[LONG_LOOP ? LA : 1], rb3[LONG_LOOP ? LB : 1];
   // operand bases of both pairs are read from the kernel arguments once, not per k-tile
   const long long lda0 = g.lda[0], lda1 = g.lda[1], ldb0 = g.ldb[0], ldb1 = g.ldb[1];
   const T* const Abase0 = (const T*)g.A[0] + (long long)m0 * lda0 + (long long)(tid / NCH) * lda0 + (tid % NCH) * EPC;
@@ -459,12 +462,10 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
     _Pragma("unroll") for (int i_ = 0; i_ < LA; ++i_) RA_[i_] = *(const u32x4*)(Ab_ + i_ * lda_);    \
     _Pragma("unroll") for (int i_ = 0; i_ < LB; ++i_) RB_[i_] = *(const u32x4*)(Bb_ + i_ * ldb_);    \
   }
-  // one k-tile: registers -> LDS, refill the registers two tiles ahead, multiply.  Every thread
-  // of the workgroup passes both barriers whether or not its group still has a tile (t_ < te).
-  // In the steady-state loop the refill is unconditional (always_), so the loop body has no branch
-  // around memory instructions: the compiler then knows exactly how many loads are in flight and
-  // waits only for the register set it is about to store.  The last stages refill conditionally.
-#define BETTY_STAGE(RA_, RB_, t_, first_, always_, buf_)                                                   \
+  // one k-tile: registers -> LDS, refill the registers dist_ tiles ahead (always_, or if that tile
+  // exists), multiply.  Every thread of the workgroup passes both barriers whether or not its group
+  // still has a tile (t_ < te).
+#define BETTY_STAGE(RA_, RB_, t_, first_, always_, dist_, buf_)                                      \
   {                                                                                                  \
     const bool live_ = KG == 1 || (t_) < te;                                                         \
     u32x4* const sA_ = sA + (DB ? (buf_) * LBUF : 0);                                                \
@@ -481,7 +482,7 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
       }                                                                                              \
     }                                                                                                \
     BETTY_GROUP_SYNC();                                                                              \
-    if ((always_) || (t_) + 2 < te) BETTY_GLOAD(RA_, RB_, (t_) + 2)                                  \
+    if ((always_) || (t_) + (dist_) < te) BETTY_GLOAD(RA_, RB_, (t_) + (dist_))                      \
     if (live_) {                                                                                     \
       _Pragma("unroll") for (int j_ = 0; j_ < NCH / 2; ++j_) {                                       \
         const int c_ = 2 * j_ + (lane >> 5);                                                         \
@@ -497,27 +498,64 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
     }                                                                                                \
   }
 
-  if (tb < te) BETTY_GLOAD(ra0, rb0, tb)
-  if (tb + 1 < te) BETTY_GLOAD(ra1, rb1, tb + 1)
-  // Unsplit launches (KG == 1) have long k loops: steady state while both refills of an iteration
-  // stay inside the k-range, then a short tail.  K-split launches run a handful of tiles per
-  // group; they keep the compact loop (less code to fetch for a kernel that lives a few us).
   const int n_full = te - tb;                       // tiles this group really has (<= NI)
-  int it = 0;
-  if constexpr (KG == 1) {
-    if (n_full > 3) {                               // first pair peeled: no barrier before the first store
-      BETTY_STAGE(ra0, rb0, tb, true, true, 0)
-      BETTY_STAGE(ra1, rb1, tb + 1, false, true, 1)
-      it = 2;
-    }
-    for (; it + 3 < n_full; it += 2) {
-      BETTY_STAGE(ra0, rb0, tb + it, false, true, 0)
-      BETTY_STAGE(ra1, rb1, tb + it + 1, false, true, 1)
+  // Long-loop form, for unsplit activation-shaped launches that leave a compute unit at most two
+  // workgroups (the host says so in batch.sparse_grid): such a launch is bound by the latency of its
+  // operand loads, so what counts is how many k-tiles are really in flight.  The compiler decides
+  // how long a wavefront waits before it stores a register set to LDS from what it can prove about
+  // the loads in flight, and where control flow merges it assumes the worst of the incoming paths:
+  // a refill inside a branch, or a loop that can be entered with other loads in flight than its
+  // back edge carries, makes every stage wait for all outstanding loads, i.e. for the tile
+  // requested one stage ago, the full memory latency every other stage (512 x 4096 x 8192:
+  // 74 us).  Here the loop is entered through straight-line code that leaves exactly the loop's own
+  // state, refills unconditionally, and keeps four register sets, so a stage waits for the oldest
+  // set only while three k-tiles stay in flight.  (With four workgroups per compute unit the same
+  // form is slower: the launch is then bound by the L1 fill rate, not by latency.)
+  bool done = false;
+  if constexpr (LONG_LOOP) {
+    if (batch.sparse_grid && n_full >= 8) {
+      BETTY_GLOAD(ra0, rb0, tb)
+      BETTY_GLOAD(ra1, rb1, tb + 1)
+      BETTY_GLOAD(ra2, rb2, tb + 2)
+      BETTY_GLOAD(ra3, rb3, tb + 3)
+      int it = 0;
+      for (; it + 7 < n_full; it += 4) {
+        BETTY_STAGE(ra0, rb0, tb + it, false, true, 4, 0)
+        BETTY_STAGE(ra1, rb1, tb + it + 1, false, true, 4, 1)
+        BETTY_STAGE(ra2, rb2, tb + it + 2, false, true, 4, 0)
+        BETTY_STAGE(ra3, rb3, tb + it + 3, false, true, 4, 1)
+      }
+      for (; it < n_full; it += 4) {                // the last four to seven tiles
+        BETTY_STAGE(ra0, rb0, tb + it, false, false, 4, 0)
+        if (it + 1 < n_full) BETTY_STAGE(ra1, rb1, tb + it + 1, false, false, 4, 1)
+        if (it + 2 < n_full) BETTY_STAGE(ra2, rb2, tb + it + 2, false, false, 4, 0)
+        if (it + 3 < n_full) BETTY_STAGE(ra3, rb3, tb + it + 3, false, false, 4, 1)
+      }
+      done = true;
     }
   }
-  for (; it < NI; it += 2) {
-    BETTY_STAGE(ra0, rb0, tb + it, it == 0, false, 0)
-    if (it + 1 < NI) BETTY_STAGE(ra1, rb1, tb + it + 1, false, false, 1)
+  if (!done) {
+    if (tb < te) BETTY_GLOAD(ra0, rb0, tb)
+    if (tb + 1 < te) BETTY_GLOAD(ra1, rb1, tb + 1)
+    // Unsplit launches (KG == 1) have long k loops: steady state while both refills of an iteration
+    // stay inside the k-range, then a short tail.  K-split launches run a handful of tiles per
+    // group; they keep the compact loop (less code to fetch for a kernel that lives a few us).
+    int it = 0;
+    if constexpr (KG == 1) {
+      if (n_full > 3) {                               // first pair peeled: no barrier before the first store
+        BETTY_STAGE(ra0, rb0, tb, true, true, 2, 0)
+        BETTY_STAGE(ra1, rb1, tb + 1, false, true, 2, 1)
+        it = 2;
+      }
+      for (; it + 3 < n_full; it += 2) {
+        BETTY_STAGE(ra0, rb0, tb + it, false, true, 2, 0)
+        BETTY_STAGE(ra1, rb1, tb + it + 1, false, true, 2, 1)
+      }
+    }
+    for (; it < NI; it += 2) {
+      BETTY_STAGE(ra0, rb0, tb + it, it == 0, false, 2, 0)
+      if (it + 1 < NI) BETTY_STAGE(ra1, rb1, tb + it + 1, false, false, 2, 1)
+    }
   }
 #undef BETTY_STAGE
 #undef BETTY_GLOAD
@@ -936,6 +974,32 @@ static void launch_one(int total, hipStream_t st, const GemmBatch& b, hipError_t
   gemm_fused_kernel<T, BT, BT, GEMM_NCH, WPG, KG, MODE><<<total, 64 * WPG * KG, lds, st>>>(b);
 }
 
+// 128 x 64 tiles, unsplit: the activation-shaped products of a grid that would otherwise leave
+// two 64-tiles per compute unit
+template <typename T, int MODE>
+static void launch_rect(int total, hipStream_t st, const GemmBatch& b, hipError_t& err) {
+  constexpr size_t lds = (size_t)2 * (128 + 64) * (GEMM_NCH + 1) * 16;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_fused_kernel<T, 128, 64, GEMM_NCH, 4, 1, MODE>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) { err = e; return; }
+    configured = true;
+  }
+  gemm_fused_kernel<T, 128, 64, GEMM_NCH, 4, 1, MODE><<<total, 256, lds, st>>>(b);
+}
+
+template <typename T>
+static void launch_rect_mode(int mode, int total, hipStream_t st, const GemmBatch& b, hipError_t& err) {
+  switch (mode) {
+#define BETTY_CASE_R(M_) case M_: launch_rect<T, M_>(total, st, b, err); break;
+    BETTY_CASE_R(EPI_FWD) BETTY_CASE_R(EPI_FWD_LAST) BETTY_CASE_R(EPI_BWD) BETTY_CASE_R(EPI_RFWD)
+    BETTY_CASE_R(EPI_RFWD_LAST) BETTY_CASE_R(EPI_RBWD) BETTY_CASE_R(EPI_RFWD_LAST_HESS)
+#undef BETTY_CASE_R
+    default: err = hipErrorInvalidValue; break;
+  }
+}
+
 template <typename T, int BT, int WPG, int KG>
 static void launch_chain_mode(int mode, int total, hipStream_t st, const GemmBatch& b, hipError_t& err) {
   switch (mode) {
@@ -997,12 +1061,14 @@ static void launch_elem(int cfg, int mode, int total, hipStream_t st, const Gemm
     case GEMM_64x1: launch_chain_mode<T, 64, 4, 1>(mode, total, st, b, err); break;
     case GEMM_64x4: launch_chain_mode<T, 64, 4, 4>(mode, total, st, b, err); break;
     case GEMM_32x8: launch_chain_mode<T, 32, 1, 8>(mode, total, st, b, err); break;
+    case GEMM_128x64: launch_rect_mode<T>(mode, total, st, b, err); break;
     default: err = hipErrorInvalidValue; break;
   }
 }
 
 int gemm_ktile_elems(Elem elem) { return GEMM_NCH * (elem == ELEM_BF16 ? 8 : 4); }
-int gemm_cfg_tile(int cfg) { return cfg == GEMM_128x1 ? 128 : cfg == GEMM_32x8 ? 32 : 64; }
+int gemm_cfg_tile(int cfg) { return cfg == GEMM_128x1 ? 128 : cfg == GEMM_32x8 ? 32 : 64; }   // (columns, for 128x64)
+static int gemm_cfg_tile_rows(int cfg) { return cfg == GEMM_128x64 ? 128 : gemm_cfg_tile(cfg); }
 static int gemm_cfg_waves(int cfg) { return cfg == GEMM_64x4 ? 16 : cfg == GEMM_32x8 ? 8 : 4; }
 
 void launch_gemm_batch(Ctx& ctx, Elem elem, int cfg, GemmBatch& b, double flops, double bytes) {
@@ -1011,10 +1077,11 @@ void launch_gemm_batch(Ctx& ctx, Elem elem, int cfg, GemmBatch& b, double flops,
   int blocks = 0;
   for (int i = 0; i < b.n; ++i) {
     b.block_begin[i] = blocks;
-    blocks += (b.p[i].g.Mp / bt) * (b.p[i].g.Np / bt);
+    blocks += (b.p[i].g.Mp / gemm_cfg_tile_rows(cfg)) * (b.p[i].g.Np / bt);
   }
   b.block_begin[b.n] = blocks;
   b.gemm_blocks = blocks;
+  b.sparse_grid = blocks <= 2 * ctx.num_cus ? 1 : 0;
   int bias_blocks = 0;
   for (int i = 0; i < b.n_bias; ++i) {
     b.bias_begin[i] = bias_blocks;

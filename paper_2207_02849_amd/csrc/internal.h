@@ -88,10 +88,11 @@ constexpr int MAX_PROBLEMS = 8;
 constexpr int GEMM_NCH = 8;              // 16-byte chunks per row of a k-tile
 // tile extent x number of K groups per workgroup; a group is 2 x 2 wavefronts, except in 32x8
 // (32-tile, eight groups of one wavefront)
-enum { GEMM_128x1 = 0, GEMM_64x1 = 2, GEMM_64x4 = 3, GEMM_32x8 = 4 };
+enum { GEMM_128x1 = 0, GEMM_64x1 = 2, GEMM_64x4 = 3, GEMM_32x8 = 4, GEMM_128x64 = 5 };
 
 struct GemmBatch {
   int n = 0, n_bias = 0, gemm_blocks = 0;
+  int sparse_grid = 0;                   // the launch leaves a compute unit at most two workgroups (set by launch_gemm_batch)
   int block_begin[MAX_PROBLEMS + 1];
   int bias_begin[MAX_PROBLEMS + 1];
   GemmProblem p[MAX_PROBLEMS];
@@ -106,6 +107,7 @@ struct Ctx {
   bool profiling = false;
   std::vector<ProfRec> recs;
   hipError_t first_error = hipSuccess;
+  int num_cus = 256;                     // compute units of the device the stream runs on
   void begin(int kind, double flops, double bytes);
   void end();
 };

@@ -588,6 +588,36 @@ def test_large_layer_weight_gradient_kernel_agrees_with_the_default_one(kind, di
     assert rel_l2(host(got["neumann4"]), orc.hypergrad_neumann(oracle_problem(wl), wl.w, wl.lam, 4, 0.05)) < 2e-2
 
 
+@pytest.mark.parametrize("kind,prec,tol,dims,batch", [("l2", "bf16", 2e-2, (300, 200, 150, 10), 130),
+                                                       ("reweight", "bf16", 2e-2, (300, 200, 150, 40), 130),
+                                                       ("l2", "fp32", 1e-4, (300, 200, 150, 10), 130),
+                                                       ("l2", "bf16", 2e-2, (1100, 260, 70, 33), 200)])
+def test_rectangular_tiles_and_long_k_loops(kind, prec, tol, dims, batch, monkeypatch):
+    """Activation-shaped products whose grid would leave a compute unit a few 64-tiles take
+    128 x 64 tiles, and unsplit launches on a sparse grid a k loop with four k-tiles in flight;
+    both are chosen from the problem size, so they are forced on here for every product of small
+    ragged models (one with a reduction of 18 k-tiles, long enough for the steady-state loop) and
+    checked against the oracle on each entry point, the replayed graph included."""
+    wl = wk.tiny(kind=kind, act="gelu", dims=dims, batch=batch, prec=prec, hidden=100)
+    prob = oracle_problem(wl)
+    w, lam = dev(wl.w), dev(wl.lam)
+    v = np.random.default_rng(5).standard_normal(wl.w.size).astype(np.float32)
+    monkeypatch.setenv("BETTY_TUNE", "rect=100000,rectk=1,blocks=1")
+    b = binding.from_workload(wl)
+    checks = {"grad": (b.betty_lower_grad(w, lam), orc.lower_grad(prob, wl.w, wl.lam)[1]),
+              "hvp": (b.betty_hvp(w, lam, dev(v)), orc.hvp(prob, wl.w, wl.lam, v)),
+              "neumann": (b.betty_hypergrad_neumann(w, lam, 3, 0.05), orc.hypergrad_neumann(prob, wl.w, wl.lam, 3, 0.05))}
+    first = checks["neumann"][0].clone()
+    again = b.betty_hypergrad_neumann(w, lam, 3, 0.05)            # replay of the captured graph
+    torch.cuda.synchronize()
+    assert torch.equal(first, again)
+    for name, (got, ref) in checks.items():
+        err = rel_l2(host(got), ref)
+        print(wl.name, name, f"{err:.2e}", flush=True)
+        assert err < tol, (name, err)
+    b.close()
+
+
 @pytest.mark.parametrize("kind", ["l2", "reweight", "proximal"])
 def test_two_stream_finite_differences_are_bit_identical_to_the_serial_ones(kind, monkeypatch):
     """Small models evaluate the lower gradient at w + eps v and at w - eps v side by side on two
