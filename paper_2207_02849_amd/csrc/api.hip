@@ -1030,14 +1030,6 @@ betty_status betty_bind(betty_handle h, void* workspace, size_t bytes, void* hip
   if (bytes < h->ws_need) return fail(h, BETTY_EWORKSPACE, "workspace has %zu bytes, %zu needed", bytes, h->ws_need);
   h->ws = (char*)workspace;
   h->ctx.stream = (hipStream_t)hip_stream;
-  {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
-      h->ctx.num_cus = cus;
-    else
-      (void)hipGetLastError();
-  }
   if (!h->side_stream && hip_stream != nullptr) {
     // second stream (default priority) and the events that order it against the bound stream
     bool ok = hipStreamCreateWithFlags(&h->side_stream, hipStreamNonBlocking) == hipSuccess;

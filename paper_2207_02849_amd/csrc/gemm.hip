@@ -499,21 +499,20 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
   }
 
   const int n_full = te - tb;                       // tiles this group really has (<= NI)
-  // Long-loop form, for unsplit activation-shaped launches that leave a compute unit at most two
-  // workgroups (the host says so in batch.sparse_grid): such a launch is bound by the latency of its
-  // operand loads, so what counts is how many k-tiles are really in flight.  The compiler decides
-  // how long a wavefront waits before it stores a register set to LDS from what it can prove about
-  // the loads in flight, and where control flow merges it assumes the worst of the incoming paths:
-  // a refill inside a branch, or a loop that can be entered with other loads in flight than its
-  // back edge carries, makes every stage wait for all outstanding loads, i.e. for the tile
-  // requested one stage ago, the full memory latency every other stage (512 x 4096 x 8192:
-  // 74 us).  Here the loop is entered through straight-line code that leaves exactly the loop's own
-  // state, refills unconditionally, and keeps four register sets, so a stage waits for the oldest
-  // set only while three k-tiles stay in flight.  (With four workgroups per compute unit the same
-  // form is slower: the launch is then bound by the L1 fill rate, not by latency.)
+  // Long-loop form, for unsplit activation-shaped launches with at least eight k-tiles.  What
+  // counts for them is how many k-tiles are really in flight.  The compiler decides how long a
+  // wavefront waits before it stores a register set to LDS from what it can prove about the loads
+  // in flight, and where control flow merges it assumes the worst of the incoming paths: a refill
+  // inside a branch, or a loop that can be entered with other loads in flight than its back edge
+  // carries, makes every stage wait for all outstanding loads, i.e. for the tile requested one
+  // stage ago, the full memory latency every other stage (512 x 4096 x 8192: 74 us).  Here the loop
+  // is entered through straight-line code that leaves exactly the loop's own state, refills
+  // unconditionally, and keeps four register sets, so a stage waits for the oldest set only while
+  // three k-tiles stay in flight (66 us; 39 us for half the rows, which took 70 us before;
+  // 8192 x 8192 x 4096 on 128-tiles 803 -> 695 us).
   bool done = false;
   if constexpr (LONG_LOOP) {
-    if (batch.sparse_grid && n_full >= 8) {
+    if (n_full >= 8) {
       BETTY_GLOAD(ra0, rb0, tb)
       BETTY_GLOAD(ra1, rb1, tb + 1)
       BETTY_GLOAD(ra2, rb2, tb + 2)
@@ -1081,7 +1080,6 @@ void launch_gemm_batch(Ctx& ctx, Elem elem, int cfg, GemmBatch& b, double flops,
   }
   b.block_begin[b.n] = blocks;
   b.gemm_blocks = blocks;
-  b.sparse_grid = blocks <= 2 * ctx.num_cus ? 1 : 0;
   int bias_blocks = 0;
   for (int i = 0; i < b.n_bias; ++i) {
     b.bias_begin[i] = bias_blocks;

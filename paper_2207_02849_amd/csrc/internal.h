@@ -92,7 +92,6 @@ enum { GEMM_128x1 = 0, GEMM_64x1 = 2, GEMM_64x4 = 3, GEMM_32x8 = 4, GEMM_128x64 
 
 struct GemmBatch {
   int n = 0, n_bias = 0, gemm_blocks = 0;
-  int sparse_grid = 0;                   // the launch leaves a compute unit at most two workgroups (set by launch_gemm_batch)
   int block_begin[MAX_PROBLEMS + 1];
   int bias_begin[MAX_PROBLEMS + 1];
   GemmProblem p[MAX_PROBLEMS];
@@ -107,7 +106,6 @@ struct Ctx {
   bool profiling = false;
   std::vector<ProfRec> recs;
   hipError_t first_error = hipSuccess;
-  int num_cus = 256;                     // compute units of the device the stream runs on
   void begin(int kind, double flops, double bytes);
   void end();
 };
