@@ -802,8 +802,10 @@ __device__ __forceinline__ void wg_finish(const WgTile& w, int pass, int pr, int
 
 // How many passes ahead the epilogue inputs are requested (the ring of register sets below holds
 // one more).  Requesting the whole tile ahead (3, affordable with two input arrays) was measured
-// slower than one pass ahead on the 121M-parameter model: 620 against 576 us per launch.
-template <int MODE, bool LAM> constexpr int wg_depth() { return 1; }
+// slower than one pass ahead on the 121M-parameter model: 620 against 576 us per launch.  The final
+// step of the series (four input arrays, once per hypergradient) requests each pass as it gets
+// to it: a second register set would not fit beside the tile walk's state.
+template <int MODE, bool LAM> constexpr int wg_depth() { return MODE == EPI_WGRAD_NEUMANN_L2 ? 0 : 1; }
 constexpr int WG_NPASS = WG_BT / WG_PASS;
 
 template <int MODE, bool LAM, bool VEC>
@@ -830,61 +832,49 @@ __global__ __launch_bounds__(256, 2) void wgrad128_kernel(GemmBatch batch) {
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
 
-  int bid = blockIdx.x;
-  if (bid >= batch.gemm_blocks) {
-    bid -= batch.gemm_blocks;
+  // The first batch.walkers workgroups (two per compute unit) walk the tiles (tile = blockIdx.x,
+  // then + walkers, ...) instead of one workgroup starting per tile, and where registers allow
+  // request the first two k-tiles of their next tile before they finish the current one
+  // (121M-parameter model: first weight-gradient launch 389 -> 370 us, Neumann launches 547 -> 536 us).
+  // The bias rows follow in workgroups of their own.
+  const int P = batch.walkers;
+  if ((int)blockIdx.x >= P) {
+    const int bid = blockIdx.x - P;
     int j = 0;
     while (j + 1 < batch.n_bias && bid >= batch.bias_begin[j + 1]) ++j;
     bias_rows<T, MODE>(batch.bias[j], (bid - batch.bias_begin[j]) * 4 + (threadIdx.x >> 6));
     return;
   }
-  int pi = 0;
-  while (pi + 1 < batch.n && bid >= batch.block_begin[pi + 1]) ++pi;
-  const GemmArgs& g = batch.p[pi].g;
-  const Epilogue& e = batch.p[pi].e;
-  const int tile = bid - batch.block_begin[pi];
-  const int tiles_n = g.Np / BT;
-  int tm = tile / tiles_n, tn = tile % tiles_n;
-  if (g.xgm > 0) {                                 // XCD-compact order (see GemmArgs)
-    const int x = tile & 7, q = tile >> 3;
-    const int rm = (g.Mp / BT) / g.xgm, rn = tiles_n / g.xgn;
-    tm = (x / g.xgn) * rm + q / rn;
-    tn = (x % g.xgn) * rn + q % rn;
-  }
-  const int m0 = tm * BT, n0 = tn * BT;
-
-  WgTile w;
-  w.C = e.C; w.v = e.v; w.p = e.p; w.out = (T*)e.out; w.outT = (T*)e.outT;
-  w.ldc = e.ldc; w.ld = e.ld; w.ldT = e.ldT;
-  w.M = g.M; w.N = g.N; w.m0 = m0; w.n0 = n0;
-  w.alpha = e.alpha; w.beta = e.beta; w.gamma = e.gamma;
-  w.has_x = e.x != nullptr;
-  if constexpr (MODE == EPI_WGRAD) { w.src[0] = e.lam; w.src[1] = e.x; w.src[2] = e.lam; w.src[3] = e.lam; }
-  else if constexpr (MODE == EPI_WGRAD_NEUMANN) { w.src[0] = e.x; w.src[1] = e.v; w.src[2] = e.lam; w.src[3] = e.x; }
-  else if constexpr (MODE == EPI_WGRAD_NEUMANN_L2) { w.src[0] = e.p; w.src[1] = e.v; w.src[2] = e.lam; w.src[3] = e.x; }
-  else if constexpr (MODE == EPI_WGRAD_SGD) { w.src[0] = e.v; w.src[1] = e.p; w.src[2] = e.lam; w.src[3] = e.x ? e.x : e.p; }
-  else { w.src[0] = w.src[1] = w.src[2] = w.src[3] = nullptr; }
-  // 16-byte accesses need every flat vector of the tile aligned and the tile inside the columns
-  unsigned long long bits = (unsigned long long)w.C | (unsigned long long)w.v | (unsigned long long)w.p;
-#pragma unroll
-  for (int k = 0; k < wg_narr<MODE, LAM>(); ++k) bits |= (unsigned long long)w.src[k];
-  const bool vec = (bits & 15) == 0 && (w.ldc & 3) == 0 && n0 + BT <= w.N;
-  // patch of this thread inside a pass: eight lanes side by side cover 32 columns of four rows
+  // patch of this thread inside an epilogue pass: eight lanes side by side cover 32 columns of four rows
   const int pc = 8 * wave + (lane & 7), pr = lane >> 3;
 
-  f32x16 acc[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-
-  const int T0 = g.Kp[0] / KT, TT = T0 + g.Kp[1] / KT;     // an even number of k-tiles (operands are padded to 128)
+  // position and operands of a tile
+  int pi, m0, n0, T0, TT;
+  long long lda0, lda1, ldb0, ldb1;
+  const T *Abase0, *Abase1, *Bbase0, *Bbase1;
+#define BETTY_WG_LOCATE(tile_)                                                                       \
+  {                                                                                                  \
+    pi = 0;                                                                                          \
+    while (pi + 1 < batch.n && (tile_) >= batch.block_begin[pi + 1]) ++pi;                           \
+    const GemmArgs& g_ = batch.p[pi].g;                                                              \
+    const int t_ = (tile_) - batch.block_begin[pi];                                                  \
+    const int tiles_n_ = g_.Np / BT;                                                                 \
+    int tm_ = t_ / tiles_n_, tn_ = t_ % tiles_n_;                                                    \
+    if (g_.xgm > 0) {                                 /* XCD-compact order (see GemmArgs) */         \
+      const int x_ = t_ & 7, q_ = t_ >> 3;                                                           \
+      const int rm_ = (g_.Mp / BT) / g_.xgm, rn_ = tiles_n_ / g_.xgn;                                \
+      tm_ = (x_ / g_.xgn) * rm_ + q_ / rn_;                                                          \
+      tn_ = (x_ % g_.xgn) * rn_ + q_ % rn_;                                                          \
+    }                                                                                                \
+    m0 = tm_ * BT; n0 = tn_ * BT;                                                                    \
+    T0 = g_.Kp[0] / KT; TT = T0 + g_.Kp[1] / KT;     /* an even number of k-tiles (operands are padded to 128) */ \
+    lda0 = g_.lda[0]; lda1 = g_.lda[1]; ldb0 = g_.ldb[0]; ldb1 = g_.ldb[1];                          \
+    Abase0 = (const T*)g_.A[0] + (long long)(m0 + tid / NCH) * lda0 + (tid % NCH) * EPC;             \
+    Abase1 = (const T*)g_.A[1] + (long long)(m0 + tid / NCH) * lda1 + (tid % NCH) * EPC;             \
+    Bbase0 = (const T*)g_.B[0] + (long long)(n0 + tid / NCH) * ldb0 + (tid % NCH) * EPC;             \
+    Bbase1 = (const T*)g_.B[1] + (long long)(n0 + tid / NCH) * ldb1 + (tid % NCH) * EPC;             \
+  }
   u32x4 ra0[LA], rb0[LA], ra1[LA], rb1[LA];
-  const long long lda0 = g.lda[0], lda1 = g.lda[1], ldb0 = g.ldb[0], ldb1 = g.ldb[1];
-  const T* const Abase0 = (const T*)g.A[0] + (long long)(m0 + tid / NCH) * lda0 + (tid % NCH) * EPC;
-  const T* const Abase1 = (const T*)g.A[1] + (long long)(m0 + tid / NCH) * lda1 + (tid % NCH) * EPC;
-  const T* const Bbase0 = (const T*)g.B[0] + (long long)(n0 + tid / NCH) * ldb0 + (tid % NCH) * EPC;
-  const T* const Bbase1 = (const T*)g.B[1] + (long long)(n0 + tid / NCH) * ldb1 + (tid % NCH) * EPC;
 #define BETTY_WG_GLOAD(RA_, RB_, t_)                                                                 \
   {                                                                                                  \
     const bool second_ = (t_) >= T0;                                                                 \
@@ -921,37 +911,90 @@ __global__ __launch_bounds__(256, 2) void wgrad128_kernel(GemmBatch batch) {
           MfmaChunk<T>::run(af_[i_], bf_[jn_], acc[i_ * 2 + jn_]);                                   \
     }                                                                                                \
   }
-  BETTY_WG_GLOAD(ra0, rb0, 0)
-  BETTY_WG_GLOAD(ra1, rb1, 1)
-  int it = 0;
-  for (; it + 2 < TT; it += 2) {
-    BETTY_WG_STAGE(ra0, rb0, it, true, 0)
-    BETTY_WG_STAGE(ra1, rb1, it + 1, true, 1)
-  }
-  // every operand load is issued: request the inputs of the first epilogue pass behind them
-  float in[wg_depth<MODE, LAM>() + 1][wg_nreg<MODE, LAM>()][4][4];
-  if (vec) {
-#pragma unroll
-    for (int q = 0; q < (wg_depth<MODE, LAM>() < 2 ? wg_depth<MODE, LAM>() : 2); ++q) wg_request<MODE, LAM, true>(w, q, pr, pc, in[q]);
-  }
-  BETTY_WG_STAGE(ra0, rb0, it, false, 0)
-  BETTY_WG_STAGE(ra1, rb1, it + 1, false, 1)
-#undef BETTY_WG_STAGE
-#undef BETTY_WG_GLOAD
 
-  // accumulators -> LDS (the operand buffers are dead): register r of lane l of block (i, j) is
-  // element [64 wm + 32 i + 8 (r / 4) + 4 (l / 32) + r % 4][64 wn + 32 j + l % 32]
-  __syncthreads();
   float* const hs = (float*)smem;
   __bf16* const sT = (__bf16*)(hs + BT * WG_HP);
+  int tile = blockIdx.x;
+  BETTY_WG_LOCATE(tile)
+  BETTY_WG_GLOAD(ra0, rb0, 0)
+  BETTY_WG_GLOAD(ra1, rb1, 1)
+  for (;;) {
+    // here the first two k-tiles of `tile` are in flight and pi, m0, n0, TT, the bases describe it
+    const Epilogue& e = batch.p[pi].e;
+    WgTile w;
+    w.C = e.C; w.v = e.v; w.p = e.p; w.out = (T*)e.out; w.outT = (T*)e.outT;
+    w.ldc = e.ldc; w.ld = e.ld; w.ldT = e.ldT;
+    w.M = batch.p[pi].g.M; w.N = batch.p[pi].g.N; w.m0 = m0; w.n0 = n0;
+    w.alpha = e.alpha; w.beta = e.beta; w.gamma = e.gamma;
+    w.has_x = e.x != nullptr;
+    if constexpr (MODE == EPI_WGRAD) { w.src[0] = e.lam; w.src[1] = e.x; w.src[2] = e.lam; w.src[3] = e.lam; }
+    else if constexpr (MODE == EPI_WGRAD_NEUMANN) { w.src[0] = e.x; w.src[1] = e.v; w.src[2] = e.lam; w.src[3] = e.x; }
+    else if constexpr (MODE == EPI_WGRAD_NEUMANN_L2) { w.src[0] = e.p; w.src[1] = e.v; w.src[2] = e.lam; w.src[3] = e.x; }
+    else if constexpr (MODE == EPI_WGRAD_SGD) { w.src[0] = e.v; w.src[1] = e.p; w.src[2] = e.lam; w.src[3] = e.x ? e.x : e.p; }
+    else { w.src[0] = w.src[1] = w.src[2] = w.src[3] = nullptr; }
+    // 16-byte accesses need every flat vector of the tile aligned and the tile inside the columns
+    unsigned long long bits = (unsigned long long)w.C | (unsigned long long)w.v | (unsigned long long)w.p;
 #pragma unroll
-  for (int ij = 0; ij < 4; ++ij)
+    for (int k = 0; k < wg_narr<MODE, LAM>(); ++k) bits |= (unsigned long long)w.src[k];
+    const bool vec = (bits & 15) == 0 && (w.ldc & 3) == 0 && n0 + BT <= w.N;
+
+    f32x16 acc[4];
 #pragma unroll
-    for (int r = 0; r < 16; ++r)
-      hs[(wm * 64 + (ij >> 1) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * WG_HP + wn * 64 + (ij & 1) * 32 + (lane & 31)] = acc[ij][r];
-  __syncthreads();
-  if (vec) wg_epilogue<MODE, LAM, true>(w, pr, pc, tid, hs, sT, in);
-  else wg_epilogue<MODE, LAM, false>(w, pr, pc, tid, hs, sT, in);
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+    int it = 0;
+    for (; it + 2 < TT; it += 2) {
+      BETTY_WG_STAGE(ra0, rb0, it, true, 0)
+      BETTY_WG_STAGE(ra1, rb1, it + 1, true, 1)
+    }
+    // every operand load is issued: request the inputs of the first epilogue pass behind them
+    float in[wg_depth<MODE, LAM>() + 1][wg_nreg<MODE, LAM>()][4][4];
+    if (vec) {
+#pragma unroll
+      for (int q = 0; q < (wg_depth<MODE, LAM>() < 2 ? wg_depth<MODE, LAM>() : 2); ++q) wg_request<MODE, LAM, true>(w, q, pr, pc, in[q]);
+    }
+    BETTY_WG_STAGE(ra0, rb0, it, false, 0)
+    BETTY_WG_STAGE(ra1, rb1, it + 1, false, 1)
+
+    // accumulators -> LDS (the operand buffers are dead): register r of lane l of block (i, j) is
+    // element [64 wm + 32 i + 8 (r / 4) + 4 (l / 32) + r % 4][64 wn + 32 j + l % 32]
+    __syncthreads();
+#pragma unroll
+    for (int ij = 0; ij < 4; ++ij)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        hs[(wm * 64 + (ij >> 1) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * WG_HP + wn * 64 + (ij & 1) * 32 + (lane & 31)] = acc[ij][r];
+    __syncthreads();
+
+    // the next tile's first two k-tiles, requested ahead of this tile's epilogue (after the last
+    // tile the same tile once more: no branch around the loads, see gemm_fused_kernel's long loop)
+    // (only in the modes whose epilogue reads nothing: with epilogue inputs in flight as well the
+    // request ahead gains nothing measurable, and with three or four input arrays there are no
+    // registers for it)
+    constexpr bool AHEAD = wg_narr<MODE, LAM>() == 0;
+    const int next = tile + P;
+    const bool more = next < batch.gemm_blocks;
+    if constexpr (AHEAD) {
+      BETTY_WG_LOCATE(more ? next : tile)
+      BETTY_WG_GLOAD(ra0, rb0, 0)
+      BETTY_WG_GLOAD(ra1, rb1, 1)
+    }
+    if (vec) wg_epilogue<MODE, LAM, true>(w, pr, pc, tid, hs, sT, in);
+    else wg_epilogue<MODE, LAM, false>(w, pr, pc, tid, hs, sT, in);
+    if (!more) break;
+    __syncthreads();                                // the next k loop writes where this epilogue read
+    tile = next;
+    if constexpr (!AHEAD) {
+      BETTY_WG_LOCATE(tile)
+      BETTY_WG_GLOAD(ra0, rb0, 0)
+      BETTY_WG_GLOAD(ra1, rb1, 1)
+    }
+  }
+#undef BETTY_WG_STAGE
+#undef BETTY_WG_GLOAD
+#undef BETTY_WG_LOCATE
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1037,7 +1080,7 @@ static void launch_wgrad128_one(int total, hipStream_t st, const GemmBatch& b, h
     if (e != hipSuccess) { err = e; return; }
     configured = true;
   }
-  wgrad128_kernel<MODE, LAM><<<total, 256, WG_LDS, st>>>(b);
+  wgrad128_kernel<MODE, LAM><<<total - b.gemm_blocks + b.walkers, 256, WG_LDS, st>>>(b);
 }
 
 // bf16 weight-gradient launches on 128-tiles; the L2-decay term (lam) is the same for every problem of a batch
@@ -1072,6 +1115,18 @@ static void launch_elem(int cfg, int mode, int total, hipStream_t st, const Gemm
   }
 }
 
+// compute units of the current device (asked once; every device of a node is the same part)
+static int resident_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cus = n;
+    else { (void)hipGetLastError(); cus = 256; }
+  }
+  return cus;
+}
+
 int gemm_ktile_elems(Elem elem) { return GEMM_NCH * (elem == ELEM_BF16 ? 8 : 4); }
 int gemm_cfg_tile(int cfg) { return cfg == GEMM_128x1 ? 128 : cfg == GEMM_32x8 ? 32 : 64; }   // (columns, for 128x64)
 static int gemm_cfg_tile_rows(int cfg) { return cfg == GEMM_128x64 ? 128 : gemm_cfg_tile(cfg); }
@@ -1087,6 +1142,7 @@ void launch_gemm_batch(Ctx& ctx, Elem elem, int cfg, GemmBatch& b, double flops,
   }
   b.block_begin[b.n] = blocks;
   b.gemm_blocks = blocks;
+  b.walkers = blocks < 2 * resident_cus() ? blocks : 2 * resident_cus();
   int bias_blocks = 0;
   for (int i = 0; i < b.n_bias; ++i) {
     b.bias_begin[i] = bias_blocks;

@@ -92,6 +92,7 @@ enum { GEMM_128x1 = 0, GEMM_64x1 = 2, GEMM_64x4 = 3, GEMM_32x8 = 4, GEMM_128x64 
 
 struct GemmBatch {
   int n = 0, n_bias = 0, gemm_blocks = 0;
+  int walkers = 0;                       // wgrad128_kernel: workgroups that walk the tiles (set by launch_gemm_batch)
   int block_begin[MAX_PROBLEMS + 1];
   int bias_begin[MAX_PROBLEMS + 1];
   GemmProblem p[MAX_PROBLEMS];
