@@ -16,8 +16,8 @@
 // workgroups was measured first: the agent-scope fences it needs write back the L2 of every XCD
 // and cost 10-80 us per launch on this chip.)
 //
-// Tiling: 4 wavefronts (2 x 2) own a BM x BN tile; a wavefront owns TM x TN MFMA blocks of
-// 32 x 32.  K is consumed in tiles of NCH 16-byte chunks per row: global -> registers
+// Tiling: 4 wavefronts (2 x 2), or 8 (4 x 2) on the 128 x 64 tiles, own a BM x BN tile; a wavefront
+// owns TM x TN MFMA blocks of 32 x 32.  K is consumed in tiles of NCH 16-byte chunks per row: global -> registers
 // -> LDS with the next tile's global loads in flight during the multiplies.  LDS rows are padded
 // by one chunk so the 16-byte fragment reads of 8 consecutive rows hit distinct banks.
 //
@@ -350,13 +350,13 @@ __device__ void bias_rows(const BiasJob& j, int row) {
 template <typename T, int BM, int BN, int NCH, int WPG, int KG, int MODE>
 __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void gemm_fused_kernel(GemmBatch batch) {
   constexpr int GT = 64 * WPG;                     // threads of one K group
-  constexpr int WM = WPG == 4 ? 2 : 1, WN = WPG == 4 ? 2 : 1;   // wavefronts of a group over the tile
+  constexpr int WM = WPG == 8 ? 4 : WPG == 4 ? 2 : 1, WN = WPG >= 4 ? 2 : 1;   // wavefronts of a group over the tile
   constexpr int ROW = NCH + 1;                     // LDS row pitch in 16-byte chunks
   constexpr int EPC = 16 / (int)sizeof(T);         // elements per chunk
   constexpr int KT = NCH * EPC;                    // elements per k-tile
   constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);   // 32x32 blocks per wavefront
   constexpr int LA = BM * NCH / GT, LB = BN * NCH / GT;
-  static_assert(WPG == 1 || WPG == 4, "a K group is one wavefront or 2 x 2 wavefronts");
+  static_assert(WPG == 1 || WPG == 4 || WPG == 8, "a K group is one wavefront, 2 x 2 or 4 x 2 wavefronts");
   static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0 && (BM * NCH) % GT == 0 && (BN * NCH) % GT == 0, "tile");
   extern __shared__ u32x4 smem[];
 
@@ -364,7 +364,7 @@ __global__ __launch_bounds__(64 * WPG * KG, (BM == 128 && KG == 1) ? 2 : 1) void
   // operand buffers.  (Wavefront-uniform values are forced into scalar registers.)
   const int kg = __builtin_amdgcn_readfirstlane(threadIdx.x / GT);
   const int tid = threadIdx.x % GT, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = WPG == 4 ? wave >> 1 : 0, wn = WPG == 4 ? wave & 1 : 0;
+  const int wm = WPG >= 4 ? wave >> 1 : 0, wn = WPG >= 4 ? wave & 1 : 0;
   // Unsplit launches keep two LDS operand buffers and alternate between them, so the stores of
   // one k-tile overlap the multiplication of the previous one and a k-tile costs one barrier.
   constexpr bool DB = KG == 1;
@@ -1023,19 +1023,21 @@ static void launch_one(int total, hipStream_t st, const GemmBatch& b, hipError_t
   gemm_fused_kernel<T, BT, BT, GEMM_NCH, WPG, KG, MODE><<<total, 64 * WPG * KG, lds, st>>>(b);
 }
 
-// 128 x 64 tiles, unsplit: the activation-shaped products of a grid that would otherwise leave
-// two 64-tiles per compute unit
+// 128 x 64 tiles, unsplit, eight wavefronts with one MFMA block each (a launch of these tiles puts
+// one workgroup on a compute unit, and two wavefronts per SIMD hide each other's barrier and LDS
+// waits: 121M-parameter model +2.3 % over four wavefronts of two blocks): the activation-shaped
+// products of a grid that would otherwise leave one to four 64-tiles per compute unit
 template <typename T, int MODE>
 static void launch_rect(int total, hipStream_t st, const GemmBatch& b, hipError_t& err) {
   constexpr size_t lds = (size_t)2 * (128 + 64) * (GEMM_NCH + 1) * 16;
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_fused_kernel<T, 128, 64, GEMM_NCH, 4, 1, MODE>,
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_fused_kernel<T, 128, 64, GEMM_NCH, 8, 1, MODE>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) { err = e; return; }
     configured = true;
   }
-  gemm_fused_kernel<T, 128, 64, GEMM_NCH, 4, 1, MODE><<<total, 256, lds, st>>>(b);
+  gemm_fused_kernel<T, 128, 64, GEMM_NCH, 8, 1, MODE><<<total, 512, lds, st>>>(b);
 }
 
 template <typename T>
