@@ -618,6 +618,67 @@ def test_rectangular_tiles_and_long_k_loops(kind, prec, tol, dims, batch, monkey
     b.close()
 
 
+def test_size_selected_kernels_on_random_ragged_shapes(monkeypatch):
+    """The kernels that the problem size selects (128 x 64 tiles, long k loops, the 128-tile
+    weight-gradient kernel, the second stream) forced onto 40 seeded random models with ragged
+    widths 3 ... 2300 and batches 7 ... 257: under each plan the lower gradient, the Hessian-vector
+    product and the Neumann hypergradient stay within the tolerance against the oracle (or within
+    1.5 x the default plan's own error where that already exceeds it), the replayed graph repeats
+    the first result bit by bit, and the 128-tile weight-gradient kernel agrees with the default one
+    to fp32 rounding.  (Smooth activations only: with ReLU a pre-activation within rounding of zero
+    turns a different summation order into a different mask.)"""
+    rng = np.random.default_rng(1)
+    edges = [3, 17, 31, 33, 64, 65, 100, 128, 129, 200, 257, 300, 520, 1100, 2300]
+
+    def gpu_all(wl, tune, K, v):
+        if tune is None:
+            monkeypatch.delenv("BETTY_TUNE", raising=False)
+        else:
+            monkeypatch.setenv("BETTY_TUNE", tune)
+        b = binding.from_workload(wl)
+        w, lam = dev(wl.w), dev(wl.lam)
+        r = {"grad": host(b.betty_lower_grad(w, lam)), "hvp": host(b.betty_hvp(w, lam, dev(v))),
+             "neumann": host(b.betty_hypergrad_neumann(w, lam, K, 0.05))}
+        r["replay"] = host(b.betty_hypergrad_neumann(w, lam, K, 0.05))
+        b.close()
+        return r
+
+    for case in range(40):
+        L = int(rng.integers(1, 4))
+        dims = tuple(int(rng.choice(edges)) for _ in range(L + 1))
+        dims = (dims[0],) + tuple(min(d, 300) for d in dims[1:])        # long reductions come from the input width
+        kind = str(rng.choice(["l2", "reweight", "proximal"]))
+        loss = str(rng.choice(["ce", "ce", "mse"]))
+        if loss == "ce" and dims[-1] < 2:
+            dims = dims[:-1] + (2,)
+        if loss == "mse" and kind == "reweight" and dims[-1] >= 64:
+            loss = "ce"                                                 # (a documented over-tolerance family)
+        prec = str(rng.choice(["fp32", "bf16"]))
+        wl = wk.tiny(kind=kind, act=str(rng.choice(["gelu", "none"])), loss=loss, dims=dims,
+                     batch=int(rng.choice([7, 31, 64, 130, 257])), prec=prec, hidden=int(rng.choice([5, 17, 100])),
+                     seed=int(rng.integers(0, 1000)))
+        prob = oracle_problem(wl)
+        K = int(rng.integers(1, 4))
+        v = np.random.default_rng(11).standard_normal(wl.d).astype(np.float32)
+        tol = 1e-4 if prec == "fp32" else 2e-2
+        ref = {"grad": orc.lower_grad(prob, wl.w, wl.lam)[1], "hvp": orc.hvp(prob, wl.w, wl.lam, v),
+               "neumann": orc.hypergrad_neumann(prob, wl.w, wl.lam, K, 0.05)}
+        base = gpu_all(wl, None, K, v)
+        plans = ["rect=100000,rectk=1,blocks=1"]
+        if prec == "bf16":
+            plans.append("wgrad128=1,rect=100000,rectk=1,blocks=1,pipe=1")
+        for plan in plans:
+            got = gpu_all(wl, plan, K, v)
+            assert np.array_equal(got["neumann"], got["replay"]), (case, wl.name, plan)
+            for k in ref:
+                e, e0 = rel_l2(got[k], ref[k]), rel_l2(base[k], ref[k])
+                assert e <= max(tol, 1.5 * e0), (case, wl.name, dims, plan, k, e, e0)
+        if prec == "bf16":
+            got = gpu_all(wl, "wgrad128=1", K, v)
+            for k in ref:
+                assert rel_l2(got[k], base[k]) < 1e-5, (case, wl.name, dims, k)
+
+
 @pytest.mark.parametrize("kind", ["l2", "reweight", "proximal"])
 def test_two_stream_finite_differences_are_bit_identical_to_the_serial_ones(kind, monkeypatch):
     """Small models evaluate the lower gradient at w + eps v and at w - eps v side by side on two
